@@ -1,0 +1,186 @@
+/*
+ * cacheback.h -- C ABI of libcacheback_verify.so: tree verification for Cacheback speculative
+ * decoding (arXiv 2511.21699) on one AMD MI355X (gfx950).
+ *
+ * One decoding step of the paper (Section 3.2) drafts a tree of tokens on the host and then
+ * verifies all of its branches in one forward pass of the model.  This library is the GPU side of
+ * that verification for one attention layer plus the final logits:
+ *
+ *   cb_verify_tree   tree attention -- every tree node attends to the KV-cached prefix and to its
+ *                    own ancestors in the draft tree (Section 3.2, "a token attends only to its
+ *                    ancestor tokens"; a node also sees itself, which makes every root-to-leaf
+ *                    path ordinary causal attention) -- followed by the greedy acceptance of
+ *                    Section 3.2: the token the model generates at a node is the first maximum of
+ *                    the node's logits row; the longest branch prefix whose draft tokens equal what
+ *                    was generated at their parents is accepted, and the pass always yields one
+ *                    more token after it.
+ *   cb_compact_kv    keeps the K/V of the accepted nodes: cache slot S+j receives slot S+path[j],
+ *                    so that the cache afterwards holds exactly the accepted sequence.  (The
+ *                    paper's prototype re-feeds accepted tokens instead, Section 3.2; this is the
+ *                    cache-side equivalent that avoids recomputing them.)
+ *
+ * Conventions
+ *   - Node 0 of every tree is the root: the last accepted token of the previous step, not yet
+ *     attended to.  The model forward has already written the K/V of tree node i of sequence b into
+ *     cache slot kv_len[b] + i.  Nodes are topologically ordered: tree_parent[0] = -1 and
+ *     0 <= tree_parent[i] < i.  The node counts include the root (the paper's total draft length
+ *     counts the non-cached token as well).
+ *   - All tensors have their innermost dimension (head_dim or vocabulary) contiguous, 16-byte
+ *     aligned base pointers, and live in DEVICE memory unless a parameter says "host".
+ *   - The caller owns every tensor, the workspace and the stream.  The library owns only cb_ctx
+ *     and a small pinned host buffer; it allocates no device memory.  cb_verify_tree never writes
+ *     the cache; cb_compact_kv writes only slots S+1 .. S+L of each sequence.
+ *   - Every function returns CB_OK or an error code, writes no outputs on error, and never aborts.
+ *     Argument checks run on the host before any launch.  cb_last_error gives a text.
+ *   - One context serves one stream at a time; calls on one context must not overlap.
+ *   - Inputs are assumed finite (no NaN/Inf); results are unspecified otherwise.
+ */
+#ifndef CACHEBACK_H
+#define CACHEBACK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cb_ctx cb_ctx; /* opaque */
+
+enum { CB_F32 = 0, CB_BF16 = 1 }; /* element types: IEEE float32, bfloat16 */
+
+enum {
+  CB_OK = 0,
+  CB_EINVAL = 1, /* null pointer, unsupported shape or type, bad batch                    */
+  CB_ETREE = 2,  /* malformed tree: root parent != -1, parent not in [0,i), too deep        */
+  CB_ECAP = 3,   /* more nodes than max_nodes, prefix + nodes beyond the cache, workspace   */
+  CB_ESTATE = 4, /* cb_compact_kv without a preceding successful verify                     */
+  CB_EHIP = 5    /* HIP runtime failure (no device, launch error); text via cb_last_error   */
+};
+
+enum { CB_LAYOUT_TOKEN_MAJOR = 0, /* [.., token, kv_head, head_dim] */
+       CB_LAYOUT_HEAD_MAJOR = 1   /* [.., kv_head, token, head_dim] */ };
+
+#define CB_MAX_NODES 256 /* nodes per tree (ancestor sets are 256-bit)         */
+#define CB_MAX_BATCH 64  /* sequences per call                                  */
+#define CB_MAX_LAYERS 64 /* cache layers per cb_compact_kv call                 */
+
+typedef struct {            /* immutable after cb_init */
+  int32_t num_q_heads;      /* Hq                                                         */
+  int32_t num_kv_heads;     /* Hkv, divides Hq (grouped-query attention when smaller)     */
+  int32_t head_dim;         /* D: 64 or 128                                               */
+  int32_t qkv_dtype;        /* CB_F32 or CB_BF16: type of q, k, v and of the attention output */
+  int32_t logits_dtype;     /* CB_F32 or CB_BF16                                          */
+  int32_t max_batch;        /* <= CB_MAX_BATCH                                            */
+  int32_t max_nodes;        /* per tree, root included, <= CB_MAX_NODES                   */
+  int32_t max_depth;        /* deepest node allowed (edges from the root)                 */
+  int32_t vocab_size;       /* V                                                          */
+  int32_t block_size;       /* 0 = contiguous cache, else tokens per block of a paged cache */
+  int32_t max_splits;       /* upper bound on KV-sequence splits per row; 0 = default (64) */
+  float softmax_scale;      /* <= 0 means 1/sqrt(head_dim)                                */
+} cb_config;
+
+typedef struct {             /* one attention layer's cache (device memory owned by the caller) */
+  void *k, *v;               /* contiguous, token-major: [B][capacity][Hkv][D]
+                                contiguous, head-major : [B][Hkv][capacity][D]
+                                paged, token-major     : [num_blocks][block_size][Hkv][D]
+                                paged, head-major      : [num_blocks][Hkv][block_size][D]      */
+  int64_t capacity_or_num_blocks;
+  const int32_t *block_table; /* device [B][max_blocks_per_seq], logical block -> physical block;
+                                 NULL for a contiguous cache.  Entries are not checked on the host;
+                                 the kernels clamp them into the pool, so a bad table gives wrong
+                                 numbers, never a fault.                                         */
+  int32_t max_blocks_per_seq;
+  int32_t layout;             /* CB_LAYOUT_*                                                    */
+} cb_kv_layer;
+
+/* Bytes of device workspace cb_init needs for this configuration.  Host only. */
+int cb_workspace_bytes(const cb_config *cfg, size_t *bytes);
+
+/* Creates a context on the current HIP device.  `workspace` is device memory of at least
+ * cb_workspace_bytes() bytes, 256-byte aligned, which the context uses until cb_destroy.
+ * Clears the workspace's counters on the default (null) stream and waits for that. */
+int cb_init(const cb_config *cfg, void *workspace, size_t workspace_bytes, cb_ctx **out);
+
+/* Host-only argument check used by cb_verify_tree (exported so it can be exercised without a GPU):
+ * shapes against the configuration, tree well-formedness, cache capacity.  `err`/`err_len` may be
+ * NULL/0; otherwise a text is written on failure. */
+int cb_check_verify_args(const cb_config *cfg, int32_t batch, const cb_kv_layer *kv,
+                         const int32_t *kv_len, const int32_t *node_offsets,
+                         const int32_t *tree_parent, char *err, size_t err_len);
+
+/*
+ * Verifies one draft tree per sequence (Section 3.2 of the paper).
+ *   q               device [sumN][Hq][D]: queries of all tree nodes, sequences back to back
+ *   kv              the layer's cache; slots [kv_len[b], kv_len[b]+N_b) hold the tree nodes' K/V
+ *   kv_len          host [batch]: KV-cached prefix lengths S_b >= 0
+ *   node_offsets    host [batch+1]: CSR offsets of each sequence's nodes, node_offsets[0] = 0
+ *   tree_parent     host [sumN]: parent of each node as an index local to its tree, -1 at roots
+ *   draft_tokens    host [sumN]: token id of each node (the root's entry is not used)
+ *   logits          device [sumN][V]: the model's output row at each node
+ *   attn_out        device [sumN][Hq][D], qkv_dtype: attention output of every node
+ *   accepted_len    host [batch]: number of accepted draft tokens L_b, 0 .. max_depth
+ *   accepted_tokens host [batch][max_depth+1]: L_b+1 tokens per sequence, the tokens generated
+ *                   at the root and at each accepted node in order (the last is the extra token a
+ *                   pass always yields); the remaining entries are set to -1
+ * Siblings may carry the same token; among accepted nodes of equal depth the lowest index wins.
+ * Synchronises `hip_stream` (a hipStream_t, NULL = the null stream) before returning.
+ */
+int cb_verify_tree(cb_ctx *ctx, void *hip_stream, int32_t batch, const void *q,
+                   const cb_kv_layer *kv, const int32_t *kv_len, const int32_t *node_offsets,
+                   const int32_t *tree_parent, const int32_t *draft_tokens, const void *logits,
+                   void *attn_out, int32_t *accepted_len, int32_t *accepted_tokens);
+
+/*
+ * Same computation with the tree and the results resident on the device and no synchronisation:
+ * only launches are enqueued on `hip_stream` (suitable for stream capture into a HIP graph).
+ * kv_len and node_offsets stay host arrays (they are shapes; they travel as kernel arguments).
+ *   d_tree_parent, d_draft_tokens   device [sumN]
+ *   d_accepted_len                  device [batch]
+ *   d_accepted_tokens               device [batch][max_depth+1]
+ * The tree's contents cannot be checked on the host here: a malformed parent entry is treated as
+ * "child of the root", nodes deeper than max_depth are never accepted, and the status word returned
+ * by cb_device_status becomes non-zero; nothing faults.
+ */
+int cb_verify_tree_device(cb_ctx *ctx, void *hip_stream, int32_t batch, const void *q,
+                          const cb_kv_layer *kv, const int32_t *kv_len,
+                          const int32_t *node_offsets, const int32_t *d_tree_parent,
+                          const int32_t *d_draft_tokens, const void *logits, void *attn_out,
+                          int32_t *d_accepted_len, int32_t *d_accepted_tokens);
+
+/*
+ * Moves the K/V of the path accepted by the last verify call of this context into place, for
+ * `num_layers` caches that share one geometry (capacity, block table, layout) and differ only in
+ * their k/v pointers: for j = 1..L_b, slot S_b+j <- slot S_b+path_b[j].  Enqueues on `hip_stream`.
+ *   new_kv_len   host [batch] or NULL: S_b + L_b + 1.  After cb_verify_tree it is filled without
+ *                waiting; after cb_verify_tree_device filling it synchronises the stream.
+ */
+int cb_compact_kv(cb_ctx *ctx, void *hip_stream, int32_t num_layers, const cb_kv_layer *layers,
+                  int32_t *new_kv_len);
+
+/* Test hooks (each synchronises the stream of the last verify call).
+ *   cb_get_path     host [batch][max_depth+1]: node indices of the accepted path, -1 padded
+ *   cb_get_argmax   host [sumN]: first-maximum index of each logits row
+ *   cb_device_status  0, or a bit mask: 1 = malformed parent entry seen, 2 = node deeper than max_depth */
+int cb_get_path(cb_ctx *ctx, int32_t *path);
+int cb_get_argmax(cb_ctx *ctx, int32_t *argmax);
+int cb_device_status(cb_ctx *ctx, int32_t *status);
+
+/* Tuning knobs for measurements; unknown names give CB_EINVAL.
+ *   "splits"     force the number of KV-sequence splits (0 = automatic)
+ *   "attn_impl"  0 = automatic, 1 = scalar kernel, 2 = MFMA kernel (bf16, head_dim 128 only) */
+int cb_set_option(cb_ctx *ctx, const char *name, int64_t value);
+
+/* Time in milliseconds the attention kernels of the last verify call took on the device (HIP
+ * events recorded around them on the call's stream); enabled with option "time_attention" = 1.
+ * Synchronises.  Not available under stream capture. */
+int cb_last_attention_ms(cb_ctx *ctx, float *ms);
+
+const char *cb_last_error(const cb_ctx *ctx); /* "" when the last call succeeded; ctx may be NULL
+                                                 for the error of a failed cb_init */
+void cb_destroy(cb_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CACHEBACK_H */

@@ -1,0 +1,258 @@
+"""ctypes binding of libcacheback_verify.so (see include/cacheback.h): argument marshalling only.
+
+Every step of the verification runs inside the library's HIP kernels; PyTorch is used here for
+device memory and streams.  Loading fails loudly when the library has not been built
+(``python -m paper_2511_21699_amd.build``); there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcacheback_verify.so")
+
+CB_F32, CB_BF16 = 0, 1
+CB_OK, CB_EINVAL, CB_ETREE, CB_ECAP, CB_ESTATE, CB_EHIP = range(6)
+CB_LAYOUT_TOKEN_MAJOR, CB_LAYOUT_HEAD_MAJOR = 0, 1
+ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_ESTATE", 5: "CB_EHIP"}
+
+EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_verify_tree", "cb_verify_tree_device",
+           "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
+           "cb_last_attention_ms", "cb_last_error", "cb_destroy"]
+
+
+class CbConfig(C.Structure):
+    _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("qkv_dtype", C.c_int32), ("logits_dtype", C.c_int32), ("max_batch", C.c_int32),
+                ("max_nodes", C.c_int32), ("max_depth", C.c_int32), ("vocab_size", C.c_int32),
+                ("block_size", C.c_int32), ("max_splits", C.c_int32), ("softmax_scale", C.c_float)]
+
+
+class CbKvLayer(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("capacity_or_num_blocks", C.c_int64),
+                ("block_table", C.c_void_p), ("max_blocks_per_seq", C.c_int32), ("layout", C.c_int32)]
+
+
+class CbError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"{ERROR_NAMES.get(code, code)}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """dlopen the HIP library; raises if it is missing (no fallback of any kind)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2511_21699_amd.build` (needs hipcc)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+    L.cb_workspace_bytes.argtypes = [C.POINTER(CbConfig), C.POINTER(C.c_size_t)]
+    L.cb_init.argtypes = [C.POINTER(CbConfig), vp, C.c_size_t, C.POINTER(vp)]
+    L.cb_check_verify_args.argtypes = [C.POINTER(CbConfig), C.c_int32, C.POINTER(CbKvLayer), i32p, i32p, i32p,
+                                       C.c_char_p, C.c_size_t]
+    L.cb_verify_tree.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, i32p, i32p, vp, vp, i32p, i32p]
+    L.cb_verify_tree_device.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, vp, vp, vp, vp, vp, vp]
+    L.cb_compact_kv.argtypes = [vp, vp, C.c_int32, C.POINTER(CbKvLayer), i32p]
+    L.cb_get_path.argtypes = [vp, i32p]
+    L.cb_get_argmax.argtypes = [vp, i32p]
+    L.cb_device_status.argtypes = [vp, i32p]
+    L.cb_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
+    L.cb_last_attention_ms.argtypes = [vp, C.POINTER(C.c_float)]
+    L.cb_last_error.argtypes = [vp]
+    L.cb_last_error.restype = C.c_char_p
+    L.cb_destroy.argtypes = [vp]
+    L.cb_destroy.restype = None
+    for name in EXPORTS:
+        if name not in ("cb_last_error", "cb_destroy"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ip(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def make_config(Hq: int, Hkv: int, D: int, qkv_dtype: str, logits_dtype: str, max_batch: int, max_nodes: int,
+                max_depth: int, vocab: int, block_size: int = 0, max_splits: int = 0,
+                softmax_scale: float = 0.0) -> CbConfig:
+    dt = {"f32": CB_F32, "bf16": CB_BF16}
+    return CbConfig(Hq, Hkv, D, dt[qkv_dtype], dt[logits_dtype], max_batch, max_nodes, max_depth, vocab,
+                    block_size, max_splits, softmax_scale)
+
+
+def kv_layer(k, v, block_table=None, layout: int = CB_LAYOUT_TOKEN_MAJOR, paged: bool = False) -> CbKvLayer:
+    """Describe one layer's cache held in torch tensors (token-major shapes as in cacheback.h)."""
+    if paged:
+        cap = k.shape[0]
+        return CbKvLayer(k.data_ptr(), v.data_ptr(), cap, block_table.data_ptr(), block_table.shape[1], layout)
+    cap = k.shape[1] if layout == CB_LAYOUT_TOKEN_MAJOR else k.shape[2]
+    return CbKvLayer(k.data_ptr(), v.data_ptr(), cap, None, 0, layout)
+
+
+def check_verify_args(cfg: CbConfig, batch: int, kv: CbKvLayer, kv_len, node_offsets, parent) -> Tuple[int, str]:
+    """Host-only argument check (no GPU needed)."""
+    L = load()
+    buf = C.create_string_buffer(256)
+    a, b, c = _i32(kv_len), _i32(node_offsets), _i32(parent)
+    rc = L.cb_check_verify_args(C.byref(cfg), batch, C.byref(kv), _ip(a), _ip(b), _ip(c), buf, 256)
+    return rc, buf.value.decode()
+
+
+def workspace_bytes(cfg: CbConfig) -> int:
+    n = C.c_size_t(0)
+    rc = load().cb_workspace_bytes(C.byref(cfg), C.byref(n))
+    if rc:
+        raise CbError(rc, load().cb_last_error(None).decode())
+    return n.value
+
+
+class Verifier:
+    """One library context plus its torch-owned workspace."""
+
+    def __init__(self, cfg: CbConfig, device: str = "cuda:0"):
+        import torch
+        self._torch = torch
+        self.L = load()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        nbytes = workspace_bytes(cfg)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) // 256 * 256
+        ctx = C.c_void_p()
+        rc = self.L.cb_init(C.byref(cfg), base, nbytes, C.byref(ctx))
+        if rc:
+            raise CbError(rc, self.L.cb_last_error(None).decode())
+        self.ctx = ctx
+        self.stride = cfg.max_depth + 1
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            self.L.cb_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _raise(self, rc: int):
+        if rc:
+            raise CbError(rc, self.L.cb_last_error(self.ctx).decode())
+
+    def _stream(self, stream) -> Optional[int]:
+        if stream is None:
+            stream = self._torch.cuda.current_stream(self.device)
+        return C.c_void_p(stream.cuda_stream)
+
+    def verify_tree(self, q, kv: CbKvLayer, kv_len, node_offsets, parent, tokens, logits, attn_out=None, stream=None):
+        """Host-array form; returns (attn_out, accepted_len[B], accepted_tokens[B, max_depth+1])."""
+        kv_len, node_offsets, parent, tokens = _i32(kv_len), _i32(node_offsets), _i32(parent), _i32(tokens)
+        batch = kv_len.shape[0]
+        if attn_out is None:
+            attn_out = self._torch.empty_like(q)
+        acc_len = np.zeros(batch, dtype=np.int32)
+        acc_tok = np.zeros((batch, self.stride), dtype=np.int32)
+        rc = self.L.cb_verify_tree(self.ctx, self._stream(stream), batch, q.data_ptr(), C.byref(kv), _ip(kv_len),
+                                   _ip(node_offsets), _ip(parent), _ip(tokens), logits.data_ptr(),
+                                   attn_out.data_ptr(), _ip(acc_len), _ip(acc_tok))
+        self._raise(rc)
+        return attn_out, acc_len, acc_tok
+
+    def verify_tree_device(self, q, kv: CbKvLayer, kv_len, node_offsets, d_parent, d_tokens, logits, attn_out,
+                           d_acc_len, d_acc_tok, stream=None):
+        """Device-resident form: enqueues launches only."""
+        kv_len, node_offsets = _i32(kv_len), _i32(node_offsets)
+        rc = self.L.cb_verify_tree_device(self.ctx, self._stream(stream), kv_len.shape[0], q.data_ptr(), C.byref(kv),
+                                          _ip(kv_len), _ip(node_offsets), d_parent.data_ptr(), d_tokens.data_ptr(),
+                                          logits.data_ptr(), attn_out.data_ptr(), d_acc_len.data_ptr(),
+                                          d_acc_tok.data_ptr())
+        self._raise(rc)
+
+    def compact_kv(self, layers: Sequence[CbKvLayer], batch: int, want_len: bool = True, stream=None):
+        arr = (CbKvLayer * len(layers))(*layers)
+        new_len = np.zeros(batch, dtype=np.int32)
+        rc = self.L.cb_compact_kv(self.ctx, self._stream(stream), len(layers), arr, _ip(new_len) if want_len else None)
+        self._raise(rc)
+        return new_len if want_len else None
+
+    def get_path(self, batch: int) -> np.ndarray:
+        out = np.zeros((batch, self.stride), dtype=np.int32)
+        self._raise(self.L.cb_get_path(self.ctx, _ip(out)))
+        return out
+
+    def get_argmax(self, total_nodes: int) -> np.ndarray:
+        out = np.zeros(total_nodes, dtype=np.int32)
+        self._raise(self.L.cb_get_argmax(self.ctx, _ip(out)))
+        return out
+
+    def device_status(self) -> int:
+        s = C.c_int32(0)
+        self._raise(self.L.cb_device_status(self.ctx, C.byref(s)))
+        return s.value
+
+    def set_option(self, name: str, value: int):
+        self._raise(self.L.cb_set_option(self.ctx, name.encode(), int(value)))
+
+    def last_attention_ms(self) -> float:
+        ms = C.c_float(0)
+        self._raise(self.L.cb_last_attention_ms(self.ctx, C.byref(ms)))
+        return ms.value
+
+
+# ----------------------------------------------------------------------------- numpy <-> torch marshalling
+def to_device(a: np.ndarray, dtype: str, device="cuda:0"):
+    """numpy (float32, or uint16 bf16 bit patterns) -> torch tensor on the GPU, bit for bit."""
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def to_host(t, dtype: str) -> np.ndarray:
+    """torch tensor -> numpy (float32, or uint16 bf16 bit patterns), bit for bit."""
+    import torch
+    if dtype == "bf16":
+        return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.detach().cpu().numpy()
+
+
+def config_for_case(case, max_splits: int = 0) -> CbConfig:
+    n = np.diff(case.node_offsets)
+    return make_config(case.Hq, case.Hkv, case.D, case.dtype, case.dtype, case.B, int(n.max()), case.max_depth,
+                       case.V, case.block_size, max_splits)
+
+
+class DeviceCase:
+    """A workload's tensors uploaded to the GPU, plus its cache descriptor."""
+
+    def __init__(self, case, device="cuda:0", layout: int = CB_LAYOUT_TOKEN_MAJOR):
+        import torch
+        self.case = case
+        self.q = to_device(case.q, case.dtype, device)
+        k, v = case.k, case.v
+        if layout == CB_LAYOUT_HEAD_MAJOR:
+            k, v = np.ascontiguousarray(k.swapaxes(1, 2)), np.ascontiguousarray(v.swapaxes(1, 2))
+        self.k = to_device(k, case.dtype, device)
+        self.v = to_device(v, case.dtype, device)
+        self.logits = to_device(case.logits, case.dtype, device)
+        self.block_table = None
+        if case.block_size > 0:
+            self.block_table = torch.from_numpy(np.ascontiguousarray(case.block_table, dtype=np.int32)).to(device)
+        self.layout = layout
+        self.kv = kv_layer(self.k, self.v, self.block_table, layout, paged=case.block_size > 0)

@@ -1,0 +1,517 @@
+// Host side of libcacheback_verify.so: argument checks, workspace layout, launch planning and the
+// extern "C" entry points declared in cacheback.h.  No arithmetic of the method happens here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "cb_internal.h"
+
+using namespace cb;
+
+namespace {
+
+thread_local char g_init_err[256] = "";
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct WsLayout {
+  size_t anc, parent, tokens, amax_partial, amax_out, path, len_ctx, res_len, res_tok, new_len, status,
+      tickets, partial, total;
+  int amax_chunks;
+  int max_total_nodes;
+  int max_splits;
+  int ticket_count;
+};
+
+int effective_max_splits(const cb_config& c) { return c.max_splits > 0 ? c.max_splits : 64; }
+
+bool config_ok(const cb_config* c, char* err, size_t n) {
+  auto fail = [&](const char* m) {
+    if (err && n) snprintf(err, n, "config: %s", m);
+    return false;
+  };
+  if (!c) return fail("null");
+  if (c->num_q_heads < 1 || c->num_kv_heads < 1 || c->num_q_heads % c->num_kv_heads != 0)
+    return fail("num_q_heads must be a positive multiple of num_kv_heads");
+  if (c->num_q_heads > 1024) return fail("num_q_heads > 1024");
+  if (c->head_dim != 64 && c->head_dim != 128) return fail("head_dim must be 64 or 128");
+  if ((c->qkv_dtype != CB_F32 && c->qkv_dtype != CB_BF16) || (c->logits_dtype != CB_F32 && c->logits_dtype != CB_BF16))
+    return fail("dtype must be CB_F32 or CB_BF16");
+  if (c->max_batch < 1 || c->max_batch > CB_MAX_BATCH) return fail("max_batch out of range");
+  if (c->max_nodes < 1 || c->max_nodes > CB_MAX_NODES) return fail("max_nodes out of range");
+  if (c->max_depth < 0 || c->max_depth >= CB_MAX_NODES) return fail("max_depth out of range");
+  if (c->vocab_size < 1) return fail("vocab_size < 1");
+  if (c->block_size < 0 || c->block_size > 65536) return fail("block_size out of range");
+  if (c->max_splits < 0 || c->max_splits > 4096) return fail("max_splits out of range");
+  return true;
+}
+
+WsLayout ws_layout(const cb_config& c) {
+  WsLayout L{};
+  const size_t mt = (size_t)c.max_batch * c.max_nodes;
+  const size_t stride = (size_t)c.max_depth + 1;
+  L.max_total_nodes = (int)mt;
+  L.max_splits = effective_max_splits(c);
+  L.amax_chunks = (int)(((int64_t)c.vocab_size + kArgmaxChunk - 1) / kArgmaxChunk);
+  const int g = c.num_q_heads / c.num_kv_heads;
+  L.ticket_count = c.max_batch * c.num_kv_heads * ((c.max_nodes * g + kRowTile - 1) / kRowTile);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  L.anc = take(mt * kAncWords * 4);
+  L.parent = take(mt * 4);
+  L.tokens = take(mt * 4);
+  L.amax_partial = take(mt * L.amax_chunks * sizeof(ArgmaxPartial));
+  L.amax_out = take(mt * 4);
+  L.path = take(c.max_batch * stride * 4);
+  L.len_ctx = take(c.max_batch * 4);
+  L.res_len = take(c.max_batch * 4);
+  L.res_tok = take(c.max_batch * stride * 4);
+  L.new_len = take(c.max_batch * 4);
+  L.status = take(4);
+  L.tickets = take((size_t)L.ticket_count * 4);
+  L.partial = take(mt * c.num_q_heads * (size_t)L.max_splits * (c.head_dim + 2) * 4);
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+struct cb_ctx {
+  cb_config cfg;
+  WsLayout lay;
+  char* ws;
+  // pinned host mirror
+  int32_t* h_parent;
+  int32_t* h_tokens;
+  int32_t* h_len;
+  int32_t* h_tok;
+  int32_t* h_path;
+  int32_t* h_argmax;
+  int32_t* h_misc;  // [0] status, [1..] new_len
+  void* h_block;
+  // state of the last verify
+  bool have_verify;
+  bool host_knows_len;
+  int batch;
+  int total_nodes;
+  SeqMeta meta;
+  int32_t last_len[CB_MAX_BATCH];
+  hipStream_t last_stream;
+  // options
+  int64_t opt_splits, opt_impl, opt_time;
+  hipEvent_t ev0, ev1;
+  bool ev_valid;
+  char err[256];
+
+  template <typename T>
+  T* dev(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+namespace {
+
+int set_err(cb_ctx* ctx, int code, const char* fmt, ...) {
+  char* dst = ctx ? ctx->err : g_init_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 256, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define CB_HIP(ctx, call)                                                                         \
+  do {                                                                                            \
+    hipError_t e__ = (call);                                                                      \
+    if (e__ != hipSuccess) return set_err(ctx, CB_EHIP, "%s: %s", #call, hipGetErrorString(e__)); \
+  } while (0)
+
+bool make_kv_addr(const cb_config& c, const cb_kv_layer& l, KvAddr* a) {
+  const int64_t D = c.head_dim, H = c.num_kv_heads;
+  a->k = l.k;
+  a->v = l.v;
+  a->block_table = l.block_table;
+  a->max_blocks = l.max_blocks_per_seq;
+  a->block_size = c.block_size;
+  a->num_blocks = c.block_size > 0 ? l.capacity_or_num_blocks : 0;
+  const int64_t tokens_per_unit = c.block_size > 0 ? c.block_size : l.capacity_or_num_blocks;
+  a->seq_stride = tokens_per_unit * H * D;
+  if (l.layout == CB_LAYOUT_TOKEN_MAJOR) {
+    a->token_stride = H * D;
+    a->head_stride = D;
+  } else if (l.layout == CB_LAYOUT_HEAD_MAJOR) {
+    a->token_stride = D;
+    a->head_stride = tokens_per_unit * D;
+  } else {
+    return false;
+  }
+  return true;
+}
+
+struct Plan {
+  int impl;    // 1 scalar, 2 MFMA
+  int nsplit;  // partial slots per row
+  int chunk;   // keys per split
+  int max_nodes, max_len;
+};
+
+Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const int32_t* node_offsets) {
+  const cb_config& c = ctx->cfg;
+  Plan p{};
+  int64_t rows = 0;
+  for (int b = 0; b < batch; b++) {
+    const int n = node_offsets[b + 1] - node_offsets[b];
+    p.max_nodes = std::max(p.max_nodes, n);
+    p.max_len = std::max(p.max_len, kv_len[b] + n);
+    rows += (int64_t)n * c.num_q_heads;
+  }
+  const bool mfma_ok = false && c.qkv_dtype == CB_BF16 && c.head_dim == 128;
+  p.impl = ctx->opt_impl == 1 ? 1 : (ctx->opt_impl == 2 ? (mfma_ok ? 2 : 1) : (mfma_ok ? 2 : 1));
+  const int max_splits = ctx->lay.max_splits;
+  int nsplit;
+  if (ctx->opt_splits > 0) {
+    nsplit = (int)std::min<int64_t>(ctx->opt_splits, max_splits);
+  } else if (p.impl == 1) {
+    // one workgroup per (row, split): aim for a few workgroups per compute unit, splits of >= 256 keys
+    const int64_t want = 2048;
+    nsplit = (int)std::max<int64_t>(1, std::min<int64_t>((want + rows - 1) / rows, (p.max_len + 255) / 256));
+  } else {
+    // one workgroup per (64-row tile, kv head, split): fill the 256 compute units about twice over
+    const int g = c.num_q_heads / c.num_kv_heads;
+    int64_t tiles = 0;
+    for (int b = 0; b < batch; b++)
+      tiles += (int64_t)(((node_offsets[b + 1] - node_offsets[b]) * g + kRowTile - 1) / kRowTile) * c.num_kv_heads;
+    const int64_t want = 512;
+    nsplit = (int)std::max<int64_t>(1, std::min<int64_t>((want + tiles - 1) / tiles, (p.max_len + 127) / 128));
+  }
+  nsplit = std::max(1, std::min(nsplit, max_splits));
+  int chunk = (p.max_len + nsplit - 1) / nsplit;
+  chunk = (chunk + 31) / 32 * 32;
+  p.chunk = std::max(chunk, 32);
+  p.nsplit = (p.max_len + p.chunk - 1) / p.chunk;
+  return p;
+}
+
+int check_common(cb_ctx* ctx, int32_t batch, const void* q, const cb_kv_layer* kv, const int32_t* kv_len,
+                 const int32_t* node_offsets, const void* logits, void* attn_out) {
+  if (!ctx) return set_err(nullptr, CB_EINVAL, "null context");
+  if (!q || !kv || !kv_len || !node_offsets || !logits || !attn_out)
+    return set_err(ctx, CB_EINVAL, "null argument");
+  if (batch < 1 || batch > ctx->cfg.max_batch) return set_err(ctx, CB_EINVAL, "batch %d outside [1, %d]", batch, ctx->cfg.max_batch);
+  if (((uintptr_t)q | (uintptr_t)kv->k | (uintptr_t)kv->v | (uintptr_t)logits | (uintptr_t)attn_out) & 15)
+    return set_err(ctx, CB_EINVAL, "device pointers must be 16-byte aligned");
+  return CB_OK;
+}
+
+// Enqueues the whole verification on `st`; the tree is already on the device.
+int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb_kv_layer* kv,
+                 const int32_t* kv_len, const int32_t* node_offsets, const int32_t* d_parent,
+                 const int32_t* d_tokens, const void* logits, void* attn_out, int32_t* d_len, int32_t* d_tok) {
+  const cb_config& c = ctx->cfg;
+  SeqMeta meta{};
+  for (int b = 0; b < batch; b++) meta.kv_len[b] = kv_len[b];
+  for (int b = 0; b <= batch; b++) meta.node_off[b] = node_offsets[b];
+  const int total = node_offsets[batch];
+  const Plan plan = plan_attention(ctx, batch, kv_len, node_offsets);
+
+  AttnParams ap{};
+  ap.q = q;
+  ap.out = attn_out;
+  if (!make_kv_addr(c, *kv, &ap.kv)) return set_err(ctx, CB_EINVAL, "unknown cache layout %d", kv->layout);
+  ap.anc = ctx->dev<uint32_t>(ctx->lay.anc);
+  ap.partial = ctx->dev<float>(ctx->lay.partial);
+  ap.tickets = ctx->dev<uint32_t>(ctx->lay.tickets);
+  ap.Hq = c.num_q_heads;
+  ap.Hkv = c.num_kv_heads;
+  ap.D = c.head_dim;
+  ap.chunk = plan.chunk;
+  ap.nsplit = plan.nsplit;
+  ap.batch = batch;
+  ap.scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
+
+  CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
+                                  ctx->dev<int32_t>(ctx->lay.status)));
+  const bool timing = ctx->opt_time != 0;
+  if (timing) CB_HIP(ctx, hipEventRecord(ctx->ev0, st));
+  if (plan.impl == 2) {
+    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, plan.max_len));
+  } else {
+    CB_HIP(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
+    if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
+  }
+  if (timing) {
+    CB_HIP(ctx, hipEventRecord(ctx->ev1, st));
+    ctx->ev_valid = true;
+  }
+  CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
+                            ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks));
+  CB_HIP(ctx, launch_accept(st, batch, meta, d_parent, d_tokens, ctx->dev<uint32_t>(ctx->lay.anc),
+                            ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, c.max_depth,
+                            ctx->dev<int32_t>(ctx->lay.amax_out), ctx->dev<int32_t>(ctx->lay.path),
+                            ctx->dev<int32_t>(ctx->lay.len_ctx), d_len, d_tok));
+  ctx->meta = meta;
+  ctx->batch = batch;
+  ctx->total_nodes = total;
+  ctx->last_stream = st;
+  ctx->have_verify = true;
+  ctx->host_knows_len = false;
+  return CB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cb_workspace_bytes(const cb_config* cfg, size_t* bytes) {
+  if (!bytes) return set_err(nullptr, CB_EINVAL, "null bytes");
+  if (!config_ok(cfg, g_init_err, sizeof g_init_err)) return CB_EINVAL;
+  *bytes = ws_layout(*cfg).total;
+  return CB_OK;
+}
+
+int cb_check_verify_args(const cb_config* cfg, int32_t batch, const cb_kv_layer* kv, const int32_t* kv_len,
+                         const int32_t* node_offsets, const int32_t* tree_parent, char* err, size_t err_len) {
+  auto fail = [&](int code, const char* fmt, ...) __attribute__((format(printf, 3, 4))) {
+    if (err && err_len) {
+      va_list ap;
+      va_start(ap, fmt);
+      vsnprintf(err, err_len, fmt, ap);
+      va_end(ap);
+    }
+    return code;
+  };
+  if (!config_ok(cfg, err, err_len)) return CB_EINVAL;
+  if (!kv || !kv_len || !node_offsets || !tree_parent) return fail(CB_EINVAL, "null argument");
+  if (batch < 1 || batch > cfg->max_batch) return fail(CB_EINVAL, "batch %d outside [1, %d]", batch, cfg->max_batch);
+  if (!kv->k || !kv->v) return fail(CB_EINVAL, "null cache pointer");
+  if (kv->layout != CB_LAYOUT_TOKEN_MAJOR && kv->layout != CB_LAYOUT_HEAD_MAJOR)
+    return fail(CB_EINVAL, "unknown cache layout %d", kv->layout);
+  if (kv->capacity_or_num_blocks < 1) return fail(CB_EINVAL, "empty cache");
+  if (cfg->block_size > 0 && (!kv->block_table || kv->max_blocks_per_seq < 1))
+    return fail(CB_EINVAL, "paged cache without a block table");
+  if (cfg->block_size == 0 && kv->block_table) return fail(CB_EINVAL, "block table given for a contiguous cache");
+  if (node_offsets[0] != 0) return fail(CB_EINVAL, "node_offsets[0] must be 0");
+  for (int b = 0; b < batch; b++) {
+    const int64_t n = (int64_t)node_offsets[b + 1] - node_offsets[b];
+    if (n < 1) return fail(CB_EINVAL, "sequence %d has no root node", b);
+    if (n > cfg->max_nodes) return fail(CB_ECAP, "sequence %d has %lld nodes, max_nodes is %d", b, (long long)n, cfg->max_nodes);
+    if (kv_len[b] < 0) return fail(CB_EINVAL, "negative kv_len[%d]", b);
+    const int64_t need = (int64_t)kv_len[b] + n;
+    const int64_t room = cfg->block_size > 0 ? (int64_t)kv->max_blocks_per_seq * cfg->block_size : kv->capacity_or_num_blocks;
+    if (need > room || need > (1ll << 30))
+      return fail(CB_ECAP, "sequence %d needs %lld cache slots, %lld available", b, (long long)need, (long long)room);
+    const int32_t* par = tree_parent + node_offsets[b];
+    if (par[0] != -1) return fail(CB_ETREE, "sequence %d: root parent is %d, not -1", b, par[0]);
+    int depth[CB_MAX_NODES];
+    depth[0] = 0;
+    for (int i = 1; i < n; i++) {
+      if (par[i] < 0 || par[i] >= i) return fail(CB_ETREE, "sequence %d: parent[%d] = %d not in [0, %d)", b, i, par[i], i);
+      depth[i] = depth[par[i]] + 1;
+      if (depth[i] > cfg->max_depth) return fail(CB_ETREE, "sequence %d: node %d at depth %d > max_depth %d", b, i, depth[i], cfg->max_depth);
+    }
+  }
+  return CB_OK;
+}
+
+int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ctx** out) {
+  g_init_err[0] = 0;
+  if (!out) return set_err(nullptr, CB_EINVAL, "null out");
+  *out = nullptr;
+  if (!config_ok(cfg, g_init_err, sizeof g_init_err)) return CB_EINVAL;
+  const WsLayout lay = ws_layout(*cfg);
+  if (!workspace || ((uintptr_t)workspace & (kAlign - 1))) return set_err(nullptr, CB_EINVAL, "workspace null or not 256-byte aligned");
+  if (workspace_bytes < lay.total) return set_err(nullptr, CB_ECAP, "workspace of %zu bytes, %zu needed", workspace_bytes, lay.total);
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return set_err(nullptr, CB_EHIP, "no HIP device");
+  cb_ctx* ctx = new (std::nothrow) cb_ctx();
+  if (!ctx) return set_err(nullptr, CB_EHIP, "out of host memory");
+  ctx->cfg = *cfg;
+  ctx->lay = lay;
+  ctx->ws = static_cast<char*>(workspace);
+  const size_t mt = lay.max_total_nodes, stride = (size_t)cfg->max_depth + 1;
+  const size_t ints = mt * 3 + cfg->max_batch * (1 + 2 * stride) + 1 + cfg->max_batch;
+  hipError_t e = hipHostMalloc(&ctx->h_block, ints * 4, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    delete ctx;
+    return set_err(nullptr, CB_EHIP, "hipHostMalloc: %s", hipGetErrorString(e));
+  }
+  int32_t* h = static_cast<int32_t*>(ctx->h_block);
+  ctx->h_parent = h; h += mt;
+  ctx->h_tokens = h; h += mt;
+  ctx->h_argmax = h; h += mt;
+  ctx->h_len = h; h += cfg->max_batch;
+  ctx->h_tok = h; h += cfg->max_batch * stride;
+  ctx->h_path = h; h += cfg->max_batch * stride;
+  ctx->h_misc = h;
+  e = hipEventCreate(&ctx->ev0);
+  if (e == hipSuccess) e = hipEventCreate(&ctx->ev1);
+  if (e == hipSuccess) e = hipMemset(ctx->ws + lay.status, 0, 4);
+  if (e == hipSuccess) e = hipMemset(ctx->ws + lay.tickets, 0, (size_t)lay.ticket_count * 4);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    (void)hipHostFree(ctx->h_block);
+    delete ctx;
+    return set_err(nullptr, CB_EHIP, "context set-up: %s", hipGetErrorString(e));
+  }
+  *out = ctx;
+  return CB_OK;
+}
+
+int cb_verify_tree_device(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, const cb_kv_layer* kv,
+                          const int32_t* kv_len, const int32_t* node_offsets, const int32_t* d_tree_parent,
+                          const int32_t* d_draft_tokens, const void* logits, void* attn_out,
+                          int32_t* d_accepted_len, int32_t* d_accepted_tokens) {
+  int rc = check_common(ctx, batch, q, kv, kv_len, node_offsets, logits, attn_out);
+  if (rc) return rc;
+  ctx->err[0] = 0;
+  if (!d_tree_parent || !d_draft_tokens || !d_accepted_len || !d_accepted_tokens)
+    return set_err(ctx, CB_EINVAL, "null argument");
+  // shapes are host data in this form too: check everything except the tree's contents
+  const cb_config& c = ctx->cfg;
+  if (!kv->k || !kv->v || kv->capacity_or_num_blocks < 1) return set_err(ctx, CB_EINVAL, "bad cache descriptor");
+  if (c.block_size > 0 && (!kv->block_table || kv->max_blocks_per_seq < 1)) return set_err(ctx, CB_EINVAL, "paged cache without a block table");
+  if (node_offsets[0] != 0) return set_err(ctx, CB_EINVAL, "node_offsets[0] must be 0");
+  for (int b = 0; b < batch; b++) {
+    const int64_t n = (int64_t)node_offsets[b + 1] - node_offsets[b];
+    if (n < 1) return set_err(ctx, CB_EINVAL, "sequence %d has no root node", b);
+    if (n > c.max_nodes) return set_err(ctx, CB_ECAP, "sequence %d has %lld nodes, max_nodes is %d", b, (long long)n, c.max_nodes);
+    if (kv_len[b] < 0) return set_err(ctx, CB_EINVAL, "negative kv_len[%d]", b);
+    const int64_t room = c.block_size > 0 ? (int64_t)kv->max_blocks_per_seq * c.block_size : kv->capacity_or_num_blocks;
+    if (kv_len[b] + n > room || kv_len[b] + n > (1ll << 30)) return set_err(ctx, CB_ECAP, "sequence %d does not fit the cache", b);
+  }
+  return run_pipeline(ctx, static_cast<hipStream_t>(hip_stream), batch, q, kv, kv_len, node_offsets, d_tree_parent,
+                      d_draft_tokens, logits, attn_out, d_accepted_len, d_accepted_tokens);
+}
+
+int cb_verify_tree(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, const cb_kv_layer* kv,
+                   const int32_t* kv_len, const int32_t* node_offsets, const int32_t* tree_parent,
+                   const int32_t* draft_tokens, const void* logits, void* attn_out, int32_t* accepted_len,
+                   int32_t* accepted_tokens) {
+  int rc = check_common(ctx, batch, q, kv, kv_len, node_offsets, logits, attn_out);
+  if (rc) return rc;
+  ctx->err[0] = 0;
+  if (!tree_parent || !draft_tokens || !accepted_len || !accepted_tokens) return set_err(ctx, CB_EINVAL, "null argument");
+  rc = cb_check_verify_args(&ctx->cfg, batch, kv, kv_len, node_offsets, tree_parent, ctx->err, sizeof ctx->err);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int total = node_offsets[batch];
+  const size_t stride = (size_t)ctx->cfg.max_depth + 1;
+  memcpy(ctx->h_parent, tree_parent, (size_t)total * 4);
+  memcpy(ctx->h_tokens, draft_tokens, (size_t)total * 4);
+  int32_t* d_parent = ctx->dev<int32_t>(ctx->lay.parent);
+  int32_t* d_tokens = ctx->dev<int32_t>(ctx->lay.tokens);
+  CB_HIP(ctx, hipMemcpyAsync(d_parent, ctx->h_parent, (size_t)total * 4, hipMemcpyHostToDevice, st));
+  CB_HIP(ctx, hipMemcpyAsync(d_tokens, ctx->h_tokens, (size_t)total * 4, hipMemcpyHostToDevice, st));
+  int32_t* d_len = ctx->dev<int32_t>(ctx->lay.res_len);
+  int32_t* d_tok = ctx->dev<int32_t>(ctx->lay.res_tok);
+  rc = run_pipeline(ctx, st, batch, q, kv, kv_len, node_offsets, d_parent, d_tokens, logits, attn_out, d_len, d_tok);
+  if (rc) return rc;
+  CB_HIP(ctx, hipMemcpyAsync(ctx->h_len, d_len, (size_t)batch * 4, hipMemcpyDeviceToHost, st));
+  CB_HIP(ctx, hipMemcpyAsync(ctx->h_tok, d_tok, (size_t)batch * stride * 4, hipMemcpyDeviceToHost, st));
+  CB_HIP(ctx, hipStreamSynchronize(st));
+  memcpy(accepted_len, ctx->h_len, (size_t)batch * 4);
+  memcpy(accepted_tokens, ctx->h_tok, (size_t)batch * stride * 4);
+  memcpy(ctx->last_len, ctx->h_len, (size_t)batch * 4);
+  ctx->host_knows_len = true;
+  return CB_OK;
+}
+
+int cb_compact_kv(cb_ctx* ctx, void* hip_stream, int32_t num_layers, const cb_kv_layer* layers, int32_t* new_kv_len) {
+  if (!ctx) return set_err(nullptr, CB_EINVAL, "null context");
+  ctx->err[0] = 0;
+  if (!ctx->have_verify) return set_err(ctx, CB_ESTATE, "cb_compact_kv needs a preceding successful verify call");
+  if (!layers || num_layers < 1 || num_layers > CB_MAX_LAYERS) return set_err(ctx, CB_EINVAL, "num_layers outside [1, %d]", CB_MAX_LAYERS);
+  const cb_config& c = ctx->cfg;
+  KvAddr addrs[CB_MAX_LAYERS];
+  for (int l = 0; l < num_layers; l++) {
+    const cb_kv_layer& y = layers[l];
+    if (!y.k || !y.v || (((uintptr_t)y.k | (uintptr_t)y.v) & 15)) return set_err(ctx, CB_EINVAL, "layer %d: null or misaligned cache pointer", l);
+    if (y.capacity_or_num_blocks != layers[0].capacity_or_num_blocks || y.block_table != layers[0].block_table ||
+        y.max_blocks_per_seq != layers[0].max_blocks_per_seq || y.layout != layers[0].layout)
+      return set_err(ctx, CB_EINVAL, "layer %d does not share the geometry of layer 0", l);
+    if (!make_kv_addr(c, y, &addrs[l])) return set_err(ctx, CB_EINVAL, "unknown cache layout %d", y.layout);
+  }
+  if (c.block_size > 0 && (!layers[0].block_table || layers[0].max_blocks_per_seq < 1)) return set_err(ctx, CB_EINVAL, "paged cache without a block table");
+  for (int b = 0; b < ctx->batch; b++) {
+    const int64_t n = ctx->meta.node_off[b + 1] - ctx->meta.node_off[b];
+    const int64_t room = c.block_size > 0 ? (int64_t)layers[0].max_blocks_per_seq * c.block_size : layers[0].capacity_or_num_blocks;
+    if (ctx->meta.kv_len[b] + n > room) return set_err(ctx, CB_ECAP, "sequence %d does not fit these caches", b);
+  }
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int eb = c.qkv_dtype == CB_F32 ? 4 : 2;
+  CB_HIP(ctx, launch_compact(st, ctx->batch, ctx->meta, addrs, num_layers, c.num_kv_heads, c.head_dim, eb, c.max_depth,
+                             ctx->dev<int32_t>(ctx->lay.path), ctx->dev<int32_t>(ctx->lay.len_ctx),
+                             ctx->dev<int32_t>(ctx->lay.new_len)));
+  if (new_kv_len) {
+    if (ctx->host_knows_len) {
+      for (int b = 0; b < ctx->batch; b++) new_kv_len[b] = ctx->meta.kv_len[b] + ctx->last_len[b] + 1;
+    } else {
+      CB_HIP(ctx, hipMemcpyAsync(ctx->h_misc + 1, ctx->dev<int32_t>(ctx->lay.new_len), (size_t)ctx->batch * 4, hipMemcpyDeviceToHost, st));
+      CB_HIP(ctx, hipStreamSynchronize(st));
+      memcpy(new_kv_len, ctx->h_misc + 1, (size_t)ctx->batch * 4);
+    }
+  }
+  return CB_OK;
+}
+
+int cb_get_path(cb_ctx* ctx, int32_t* path) {
+  if (!ctx || !path) return set_err(ctx, CB_EINVAL, "null argument");
+  if (!ctx->have_verify) return set_err(ctx, CB_ESTATE, "no verify call yet");
+  const size_t n = (size_t)ctx->batch * (ctx->cfg.max_depth + 1);
+  CB_HIP(ctx, hipMemcpyAsync(ctx->h_path, ctx->dev<int32_t>(ctx->lay.path), n * 4, hipMemcpyDeviceToHost, ctx->last_stream));
+  CB_HIP(ctx, hipStreamSynchronize(ctx->last_stream));
+  memcpy(path, ctx->h_path, n * 4);
+  return CB_OK;
+}
+
+int cb_get_argmax(cb_ctx* ctx, int32_t* argmax) {
+  if (!ctx || !argmax) return set_err(ctx, CB_EINVAL, "null argument");
+  if (!ctx->have_verify) return set_err(ctx, CB_ESTATE, "no verify call yet");
+  const size_t n = (size_t)ctx->total_nodes;
+  CB_HIP(ctx, hipMemcpyAsync(ctx->h_argmax, ctx->dev<int32_t>(ctx->lay.amax_out), n * 4, hipMemcpyDeviceToHost, ctx->last_stream));
+  CB_HIP(ctx, hipStreamSynchronize(ctx->last_stream));
+  memcpy(argmax, ctx->h_argmax, n * 4);
+  return CB_OK;
+}
+
+int cb_device_status(cb_ctx* ctx, int32_t* status) {
+  if (!ctx || !status) return set_err(ctx, CB_EINVAL, "null argument");
+  hipStream_t st = ctx->have_verify ? ctx->last_stream : nullptr;
+  CB_HIP(ctx, hipMemcpyAsync(ctx->h_misc, ctx->dev<int32_t>(ctx->lay.status), 4, hipMemcpyDeviceToHost, st));
+  CB_HIP(ctx, hipStreamSynchronize(st));
+  *status = ctx->h_misc[0];
+  CB_HIP(ctx, hipMemsetAsync(ctx->dev<int32_t>(ctx->lay.status), 0, 4, st));  // reading clears the sticky word
+  CB_HIP(ctx, hipStreamSynchronize(st));
+  return CB_OK;
+}
+
+int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
+  if (!ctx || !name) return set_err(ctx, CB_EINVAL, "null argument");
+  if (!strcmp(name, "splits")) ctx->opt_splits = value;
+  else if (!strcmp(name, "attn_impl")) ctx->opt_impl = value;
+  else if (!strcmp(name, "time_attention")) ctx->opt_time = value;
+  else return set_err(ctx, CB_EINVAL, "unknown option '%s'", name);
+  return CB_OK;
+}
+
+int cb_last_attention_ms(cb_ctx* ctx, float* ms) {
+  if (!ctx || !ms) return set_err(ctx, CB_EINVAL, "null argument");
+  if (!ctx->ev_valid) return set_err(ctx, CB_ESTATE, "option time_attention was not set for the last verify");
+  CB_HIP(ctx, hipEventSynchronize(ctx->ev1));
+  CB_HIP(ctx, hipEventElapsedTime(ms, ctx->ev0, ctx->ev1));
+  return CB_OK;
+}
+
+const char* cb_last_error(const cb_ctx* ctx) { return ctx ? ctx->err : g_init_err; }
+
+void cb_destroy(cb_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipEventDestroy(ctx->ev0);
+  (void)hipEventDestroy(ctx->ev1);
+  (void)hipHostFree(ctx->h_block);
+  delete ctx;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Internal declarations shared by the host API and the kernel translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "cacheback.h"
+
+namespace cb {
+
+constexpr int kAncWords = CB_MAX_NODES / 32;  // 256-bit ancestor set per node
+constexpr int kArgmaxChunk = 8192;            // logits elements scanned by one workgroup
+constexpr int kRowTile = 64;                  // query rows per workgroup in the MFMA attention
+
+// Per-sequence shapes; passed to kernels by value (kernel arguments), so they need no upload and
+// are captured with the launch.
+struct SeqMeta {
+  int32_t kv_len[CB_MAX_BATCH];
+  int32_t node_off[CB_MAX_BATCH + 1];
+};
+
+// How to find cache slot (sequence, slot, kv head) in one layer; strides in elements.
+struct KvAddr {
+  const void* k;
+  const void* v;
+  const int32_t* block_table;
+  int64_t seq_stride;    // contiguous: per sequence; paged: per physical block
+  int64_t token_stride;
+  int64_t head_stride;
+  int64_t num_blocks;    // paged: pool size (block ids are clamped into it)
+  int32_t max_blocks;    // paged: row length of the block table
+  int32_t block_size;    // 0 = contiguous
+};
+
+__device__ __forceinline__ int64_t slot_offset(const KvAddr& a, int seq, int slot, int head) {
+  if (a.block_size > 0) {
+    int lb = slot / a.block_size;
+    int64_t blk = a.block_table[(int64_t)seq * a.max_blocks + lb];
+    blk = blk < 0 ? 0 : (blk >= a.num_blocks ? a.num_blocks - 1 : blk);
+    return blk * a.seq_stride + (int64_t)(slot - lb * a.block_size) * a.token_stride +
+           (int64_t)head * a.head_stride;
+  }
+  return (int64_t)seq * a.seq_stride + (int64_t)slot * a.token_stride + (int64_t)head * a.head_stride;
+}
+
+struct AttnParams {
+  const void* q;     // [sumN][Hq][D]
+  void* out;         // [sumN][Hq][D]
+  KvAddr kv;
+  const uint32_t* anc;  // [sumN][kAncWords]
+  float* partial;       // [sumN*Hq][nsplit][D+2]: o[D] (unnormalised), m, l
+  uint32_t* tickets;    // one counter per (sequence, kv head, row tile)
+  int32_t Hq, Hkv, D;
+  int32_t chunk;        // keys per split
+  int32_t nsplit;       // partial slots per row (>= splits any sequence uses)
+  int32_t batch;
+  float scale;
+};
+
+struct ArgmaxPartial {
+  float value;
+  int32_t index;
+};
+
+// ---- launchers (defined in the .hip files); all enqueue on `st` and return the launch status
+hipError_t launch_tree_prepare(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
+                               int max_depth, uint32_t* anc, int32_t* status);
+hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows, int64_t V,
+                         ArgmaxPartial* partial, int nchunks);
+hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
+                         const int32_t* tokens, const uint32_t* anc, const ArgmaxPartial* partial,
+                         int nchunks, int max_depth, int32_t* argmax_out, int32_t* path,
+                         int32_t* len_ctx, int32_t* len_user, int32_t* tok_user);
+hipError_t launch_compact(hipStream_t st, int batch, const SeqMeta& meta, const KvAddr* layers,
+                          int num_layers, int Hkv, int D, int elem_bytes, int max_depth,
+                          const int32_t* path, const int32_t* acc_len, int32_t* new_len);
+hipError_t launch_attn_simt(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype,
+                            int max_nodes_in_call);
+hipError_t launch_merge(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype, int total_nodes);
+hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
+                            int max_len_in_call);
+
+}  // namespace cb

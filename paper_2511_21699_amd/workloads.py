@@ -16,6 +16,7 @@ bf16 tensors are carried as ``uint16`` bit patterns (numpy has no bfloat16).
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional, Tuple
 
@@ -48,22 +49,35 @@ def to_f64(a: np.ndarray, dtype: str) -> np.ndarray:
     return np.asarray(a, dtype=np.float32).astype(np.float64)
 
 
+_SLAB = 1 << 23
+
+
 def _normal(rng: np.random.Generator, shape, dtype: str, scale: float = 1.0) -> np.ndarray:
-    """N(0, scale^2) drawn in float32, rounded (RNE) to bf16 when asked; large draws go in slabs."""
+    """N(0, scale^2) drawn in float32, rounded (RNE) to bf16 when asked.
+
+    Small tensors come straight from ``rng``.  Large ones are cut into fixed slabs, each drawn from
+    its own generator keyed by (one 63-bit draw from ``rng``, slab index), so the result does not
+    depend on how many threads fill the slabs."""
     n = int(np.prod(shape))
-    if dtype == "f32":
-        out = rng.standard_normal(n, dtype=np.float32)
-        if scale != 1.0:
-            out *= np.float32(scale)
-        return out.reshape(shape)
-    out = np.empty(n, dtype=np.uint16)
-    slab = 1 << 24
-    for s in range(0, n, slab):
-        e = min(n, s + slab)
-        x = rng.standard_normal(e - s, dtype=np.float32)
+    if n <= _SLAB:
+        x = rng.standard_normal(n, dtype=np.float32)
         if scale != 1.0:
             x *= np.float32(scale)
-        out[s:e] = f32_to_bf16_bits(x)
+        return (x if dtype == "f32" else f32_to_bf16_bits(x)).reshape(shape)
+    key = int(rng.integers(0, 2 ** 63 - 1))
+    out = np.empty(n, dtype=np.float32 if dtype == "f32" else np.uint16)
+
+    def fill(s: int) -> None:
+        e = min(n, s + _SLAB)
+        g = np.random.Generator(np.random.PCG64(np.random.SeedSequence([key, s // _SLAB])))
+        x = g.standard_normal(e - s, dtype=np.float32)
+        if scale != 1.0:
+            x *= np.float32(scale)
+        out[s:e] = x if dtype == "f32" else f32_to_bf16_bits(x)
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(fill, range(0, n, _SLAB)))
     return out.reshape(shape)
 
 

@@ -1,0 +1,195 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+inputs.  Integer results (argmax, accepted length/tokens/path, compacted K/V bytes) must be
+bit-exact; attention must be within the tolerances in gpu_harness.TOL."""
+import numpy as np
+import pytest
+
+from paper_2511_21699_amd import binding as B
+from paper_2511_21699_amd import workloads as W
+from tests.gpu_harness import run_case, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+# ---------------------------------------------------------------- sizes the oracle finishes whole
+def test_config1_tiny_fp32_full():
+    for off in range(4):
+        r = run_case(W.make_config(1, seed_offset=off), what=f"cfg1 seed+{off}")
+    assert r["scale_free_err"] < 1e-5
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+def test_config2_7b_shape_full(impl):
+    run_case(W.make_config(2), options={"attn_impl": impl}, what=f"cfg2 impl={impl}")
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+def test_config2_peaked_softmax(impl):
+    # queries scaled so the softmax concentrates: outputs are O(1) and the tolerance bites
+    run_case(W.make_config(2, peaked=True, S=700), options={"attn_impl": impl}, what=f"cfg2 peaked impl={impl}")
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+def test_config3_gqa_reduced_prefix(impl):
+    run_case(W.make_config(3, S=1500), options={"attn_impl": impl}, what=f"cfg3 S=1500 impl={impl}")
+    run_case(W.make_config(3, S=777, peaked=True), options={"attn_impl": impl}, what=f"cfg3 S=777 peaked impl={impl}")
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+def test_config4_ragged_paged_reduced(impl):
+    run_case(W.make_config(4, B=5, S=(100, 1500), Hq=8, Hkv=8), options={"attn_impl": impl},
+             what=f"cfg4 reduced impl={impl}")
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+def test_config5_long_reduced(impl):
+    run_case(W.make_config(5, S=3000, Hq=8, Hkv=8, V=128256, N=256), options={"attn_impl": impl},
+             what=f"cfg5 reduced impl={impl}")
+
+
+# ---------------------------------------------------------------- full sizes, sampled rows
+def test_config3_gqa_full_size_sampled():
+    case = W.make_config(3)
+    run_case(case, rows=sample_rows(case, 256), what="cfg3 full")
+
+
+def test_config4_ragged_full_size_sampled():
+    case = W.make_config(4)
+    run_case(case, rows=sample_rows(case, 160), max_splits=72, what="cfg4 full")
+
+
+def test_config5_long_full_size_sampled():
+    case = W.make_config(5)
+    run_case(case, rows=sample_rows(case, 48), what="cfg5 full")
+
+
+# ---------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128)])
+def test_single_node_tree_and_empty_prefix(dtype, D):
+    run_case(W.custom_case(31, dtype, 2, 4, 2, D, 300, [0, 5], [[-1], [-1]]), what="single node")
+    run_case(W.custom_case(32, dtype, 1, 4, 4, D, 300, [0], [W.chain_tree(9)]), what="empty prefix chain")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_max_nodes_chain_and_star(dtype):
+    run_case(W.custom_case(33, dtype, 1, 2, 2, 128, 500, [131], [W.chain_tree(256)], p_match=0.97), what="chain 256")
+    run_case(W.custom_case(34, dtype, 1, 2, 1, 128, 500, [77], [W.star_tree(256)]), what="star 256")
+
+
+@pytest.mark.parametrize("S", [1, 31, 32, 33, 255, 257, 1023])
+def test_ragged_prefix_lengths_around_tile_edges(S):
+    rng = np.random.default_rng(S)
+    par = W.random_tree(rng, 70, 4, 7, False)[0]
+    run_case(W.custom_case(40 + S, "bf16", 1, 4, 2, 128, 1000, [S], [par], q_scale=3.0), what=f"S={S}")
+
+
+@pytest.mark.parametrize("splits", [1, 2, 5, 13])
+def test_split_counts_agree_with_the_oracle(splits):
+    rng = np.random.default_rng(5)
+    par = W.random_tree(rng, 64, 4, 6, False)[0]
+    case = W.custom_case(50, "bf16", 1, 8, 8, 128, 1000, [1000], [par], q_scale=2.0)
+    run_case(case, options={"splits": splits}, what=f"splits={splits}")
+
+
+@pytest.mark.parametrize("layout", [B.CB_LAYOUT_TOKEN_MAJOR, B.CB_LAYOUT_HEAD_MAJOR])
+@pytest.mark.parametrize("paged", [False, True])
+def test_cache_layouts(layout, paged):
+    rng = np.random.default_rng(6)
+    pars = [W.random_tree(rng, n, 3, 6, False)[0] for n in (40, 17, 64)]
+    case = W.custom_case(60, "bf16", 3, 8, 2, 128, 2000, [300, 45, 1000], pars, paged=paged)
+    run_case(case, layout=layout, what=f"layout={layout} paged={paged}")
+
+
+def test_argmax_ties_and_odd_vocab():
+    # coarse logits: the row maximum repeats many times; vocabulary not a multiple of the vector width
+    rng = np.random.default_rng(7)
+    par = W.random_tree(rng, 50, 4, 6, False)[0]
+    for dtype in ("bf16", "f32"):
+        case = W.custom_case(70, dtype, 1, 2, 2, 64, 33333, [10], [par])
+        x = np.round(rng.standard_normal(case.logits.shape, dtype=np.float32) * 2) / 2
+        x[3, :] = -0.0; x[3, 9000] = 0.0
+        x[4, :] = 1.5
+        x[5, -1] = 9.0
+        x[6, [8191, 8192]] = 9.0
+        case.logits = W.f32_to_bf16_bits(x) if dtype == "bf16" else x
+        run_case(case, what=f"ties {dtype}")
+
+
+def test_non_ancestor_keys_do_not_leak_on_gpu():
+    """Changing K/V of nodes that are not ancestors of node i leaves node i's output bit-identical."""
+    import torch
+    rng = np.random.default_rng(8)
+    par = W.random_tree(rng, 64, 4, 6, False)[0]
+    case = W.custom_case(80, "bf16", 1, 4, 4, 128, 100, [500], [par], q_scale=2.0)
+    target = 37
+    anc, x = set(), target
+    while x >= 0:
+        anc.add(x); x = int(par[x])
+    outs = []
+    for poke in (False, True):
+        c2 = case
+        if poke:
+            k, v = case.k.copy(), case.v.copy()
+            for a in range(64):
+                if a not in anc:
+                    k[0, 500 + a] = W.f32_to_bf16_bits(np.full(k.shape[2:], 30.0, dtype=np.float32))
+                    v[0, 500 + a] = W.f32_to_bf16_bits(np.full(v.shape[2:], -7.0, dtype=np.float32))
+            import copy
+            c2 = copy.copy(case); c2.k, c2.v = k, v
+        dc = B.DeviceCase(c2)
+        ver = B.Verifier(B.config_for_case(c2))
+        out, _, _ = ver.verify_tree(dc.q, dc.kv, c2.kv_len, c2.node_offsets, c2.parent, c2.tokens, dc.logits)
+        outs.append(B.to_host(out, "bf16")[target].copy())
+        ver.close()
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_multi_layer_compaction_and_device_form():
+    """cb_verify_tree_device leaves its results on the device; cb_compact_kv moves several layers at once."""
+    import torch
+    from oracle import cb_oracle as O
+    rng = np.random.default_rng(9)
+    pars = [W.chain_tree(30), W.random_tree(rng, 48, 3, 6, False)[0]]
+    case = W.custom_case(90, "bf16", 2, 4, 2, 128, 64, [37, 120], pars, paged=True, p_match=0.9)
+    dc = B.DeviceCase(case)
+    layers_k = [dc.k] + [torch.randn_like(dc.k) for _ in range(2)]
+    layers_v = [dc.v] + [torch.randn_like(dc.v) for _ in range(2)]
+    before = [(B.to_host(k, "bf16").copy(), B.to_host(v, "bf16").copy()) for k, v in zip(layers_k, layers_v)]
+    ver = B.Verifier(B.config_for_case(case))
+    d_par = torch.from_numpy(case.parent).cuda(); d_tok = torch.from_numpy(case.tokens).cuda()
+    out = torch.empty_like(dc.q)
+    d_len = torch.zeros(2, dtype=torch.int32, device="cuda")
+    d_acc = torch.zeros(2, case.max_depth + 1, dtype=torch.int32, device="cuda")
+    ver.verify_tree_device(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits, out, d_len, d_acc)
+    new_len = ver.compact_kv([B.kv_layer(k, v, dc.block_table, paged=True) for k, v in zip(layers_k, layers_v)], 2)
+    torch.cuda.synchronize()
+    a_ref, res = O.verify(case)
+    assert d_len.cpu().tolist() == [r[0] for r in res] and max(r[0] for r in res) >= 3
+    for b, (L, path, toks) in enumerate(res):
+        assert d_acc[b, :L + 1].cpu().tolist() == toks.tolist()
+        assert new_len[b] == case.kv_len[b] + L + 1
+    import copy
+    for (k0, v0), kg, vg in zip(before, layers_k, layers_v):
+        c2 = copy.copy(case); c2.k, c2.v = k0, v0
+        for b, (L, path, toks) in enumerate(res):
+            O.compact(c2, k0, v0, b, path)
+        assert np.array_equal(B.to_host(kg, "bf16"), k0) and np.array_equal(B.to_host(vg, "bf16"), v0)
+    ver.close()
+
+
+def test_error_paths_leave_outputs_alone():
+    import torch
+    case = W.custom_case(95, "f32", 1, 2, 2, 64, 50, [10], [W.chain_tree(5)])
+    dc = B.DeviceCase(case)
+    ver = B.Verifier(B.config_for_case(case))
+    with pytest.raises(B.CbError) as e:
+        ver.compact_kv([dc.kv], 1)
+    assert e.value.code == B.CB_ESTATE
+    bad = case.parent.copy(); bad[3] = 3
+    with pytest.raises(B.CbError) as e:
+        ver.verify_tree(dc.q, dc.kv, case.kv_len, case.node_offsets, bad, case.tokens, dc.logits)
+    assert e.value.code == B.CB_ETREE
+    with pytest.raises(B.CbError) as e:
+        ver.verify_tree(dc.q, dc.kv, [10 + 100], case.node_offsets, case.parent, case.tokens, dc.logits)
+    assert e.value.code == B.CB_ECAP
+    ver.close()
