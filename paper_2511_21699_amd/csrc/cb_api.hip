@@ -167,7 +167,7 @@ Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const i
     p.max_len = std::max(p.max_len, kv_len[b] + n);
     rows += (int64_t)n * c.num_q_heads;
   }
-  const bool mfma_ok = false && c.qkv_dtype == CB_BF16 && c.head_dim == 128;
+  const bool mfma_ok = c.qkv_dtype == CB_BF16 && c.head_dim == 128;
   p.impl = ctx->opt_impl == 1 ? 1 : (ctx->opt_impl == 2 ? (mfma_ok ? 2 : 1) : (mfma_ok ? 2 : 1));
   const int max_splits = ctx->lay.max_splits;
   int nsplit;
@@ -235,8 +235,9 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
                                   ctx->dev<int32_t>(ctx->lay.status)));
   const bool timing = ctx->opt_time != 0;
   if (timing) CB_HIP(ctx, hipEventRecord(ctx->ev0, st));
-  if (plan.impl == 2) {
-    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, plan.max_len));
+  if (plan.impl == 2 && attn_mfma_supports(ap)) {
+    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes));
+    if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
   } else {
     CB_HIP(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
     if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));

@@ -1,5 +1,372 @@
-// MFMA tree attention (bf16, head_dim 128) -- placeholder until the kernel lands.
+// Tree-masked flash-decode attention on the matrix cores (bf16, head_dim 128), gfx950 only.
+//
+// Tree attention, Section 3.2 of the paper: node i attends to the KV-cached prefix (slots 0..S-1)
+// and to the tree nodes on its own ancestor chain (slots S+a, a in anc(i)).  For one kv head the
+// g*N query rows (g query heads per kv head, N nodes) form a small dense matrix, so QK^T and PV are
+// MFMA contractions; the KV sequence is split across workgroups and the partial softmax states
+// (o, m, l) are merged afterwards.
+//
+// Work decomposition: one workgroup (4 wavefronts) per (sequence, kv head, 64*R-row tile, split).
+// Wave w owns 16*R rows and sweeps every key of the split, so its softmax state never has to be
+// combined with another wave's.  K/V tiles of 32 keys are brought straight from HBM into an
+// NS-deep LDS ring with global_load_lds (no registers held by loads in flight) and are shared by
+// the four waves.
+//
+// Register layouts (v_mfma_f32_16x16x32_bf16; lane l, c = l%16, kg = l/16):
+//   scores are computed transposed, S^T = K Q^T: A = K rows (key c of the sub-tile, dims
+//   8kg..8kg+7 of the 32-dim step), B = Q^T (query c, same dims), D[v] = S^T[key 4kg+v][query c].
+//   A lane therefore holds 4 keys x 1 query per 16-key sub-tile: softmax statistics are per-lane
+//   scalars shared by the 4 lanes with equal c.
+//   O^T = V^T P^T: B = P^T packs the lane's 8 probabilities of a 32-key tile (element e <-> key
+//   16(e/4)+4kg+e%4), A = V^T must hold the same keys for dim c of the 16-dim tile; it is fetched
+//   from the row-major V tile with ds_read_b64_tr_b16 (each 16-lane group reads a 4-key x 16-dim
+//   block and receives it transposed).  D[v] = O^T[dim 4kg+v][query c].
 #include "cb_internal.h"
+
 namespace cb {
-hipError_t launch_attn_mfma(hipStream_t, const AttnParams&, const SeqMeta&, int, int) { return hipErrorNotSupported; }
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+
+constexpr int kStageKeys = 32;                 // keys per LDS stage
+constexpr int kStageVecs = kStageKeys * 16;    // 16-byte pieces per K (or V) stage: 32 rows x 256 B
+constexpr int NS = 4;                          // ring depth: NS-1 stages in flight
+constexpr int kMaxBtLds = 1024;                // block-table entries staged in LDS per split
+
+// One __shared__ object per ring slot: the compiler tracks LDS-DMA completion per object.
+#define CB_DECL_RING()                                        \
+  __shared__ uint4 K0[kStageVecs], K1[kStageVecs], K2[kStageVecs], K3[kStageVecs]; \
+  __shared__ uint4 V0[kStageVecs], V1[kStageVecs], V2[kStageVecs], V3[kStageVecs];
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  // s_waitcnt simm16 on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ uint16_t f2bf(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+struct KeyAddr {  // resolves cache slots of one (sequence, kv head) to byte offsets
+  const KvAddr* kv;
+  const int* bt;   // LDS copy of this split's slice of the block table (paged caches)
+  int bt_first;    // logical block of bt[0]
+  int bs_shift;    // log2(block_size)
+  int seq, head;
+  __device__ __forceinline__ int64_t byte_off(int slot) const {
+    const KvAddr& a = *kv;
+    if (a.block_size > 0) {
+      const int lb = slot >> bs_shift;
+      int64_t blk = bt[lb - bt_first];
+      blk = blk < 0 ? 0 : (blk >= a.num_blocks ? a.num_blocks - 1 : blk);
+      return (blk * a.seq_stride + (int64_t)(slot - (lb << bs_shift)) * a.token_stride +
+              (int64_t)head * a.head_stride) * 2;
+    }
+    return ((int64_t)seq * a.seq_stride + (int64_t)slot * a.token_stride + (int64_t)head * a.head_stride) * 2;
+  }
+};
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for every
+// outstanding global->LDS load (vmcnt 0) and serialise the ring.  Ordering of LDS traffic is by
+// construction: a wave waits for its own loads of the stage (s_waitcnt vmcnt) before the barrier,
+// and every LDS read of the previous stage has been consumed by an MFMA before it.  The empty asm
+// statements stop the compiler from moving memory accesses across.
+__device__ __forceinline__ void ring_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Wave `w` brings rows 8w..8w+7 of stage `s` (keys key0..key0+31) into the ring slot: two 1 KiB
+// loads for K and two for V.  LDS position of a 16-byte piece is fixed by the lane (row*16 + c);
+// which piece of the row lands there is chosen by the XOR swizzle so that the MFMA operand reads
+// below are free of bank conflicts.  Keys past the end are clamped to the last valid one (they
+// are masked in the softmax), so every address stays inside the cache.
+__device__ __forceinline__ void issue_stage(uint4* kdst, uint4* vdst, const KeyAddr& ka, const char* kbase,
+                                            const char* vbase, int key0, int last_key, int w, int l) {
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int r = 8 * w + 4 * i + (l >> 4);
+    const int c = l & 15;
+    int key = key0 + r;
+    key = key > last_key ? last_key : key;
+    const int64_t off = ka.byte_off(key);
+    const int pk = c ^ (r & 15);
+    const int pv = c ^ ((r & 7) << 1);
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(kbase + off + pk * 16),
+                                     (__attribute__((address_space(3))) void*)(kdst + (8 * w + 4 * i) * 16), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(vbase + off + pv * 16),
+                                     (__attribute__((address_space(3))) void*)(vdst + (8 * w + 4 * i) * 16), 16, 0, 0);
+  }
+}
+
+template <int R>
+struct WaveState {
+  bf16x8 q[R][4];      // B operands of QK^T: query c, dims 32*ds + 8kg ..
+  floatx4 o[R][8];     // O^T accumulators, 8 dim tiles of 16
+  float m[R], lsum[R]; // running max (log2 domain) and this lane's share of the denominator
+};
+
+// One 32-key stage for the 16*R rows of a wave.
+template <int R>
+__device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, const uint4* __restrict__ vs,
+                                              WaveState<R>& st, float scale_log2, int key0, int S, int kend,
+                                              bool need_mask, const uint32_t* anc_lds, const int* row_node, int l) {
+  const int c = l & 15, kg = l >> 4;
+  floatx4 s[R][2];
+#pragma unroll
+  for (int rr = 0; rr < R; rr++) {
+    s[rr][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+    s[rr][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int sub = 0; sub < 2; sub++) {
+    const int row = 16 * sub + c;
+#pragma unroll
+    for (int ds = 0; ds < 4; ds++) {
+      const int piece = kg + 4 * ds;
+      const uint4 raw = ks[row * 16 + (piece ^ (row & 15))];
+      const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+      for (int rr = 0; rr < R; rr++)
+        s[rr][sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, st.q[rr][ds], s[rr][sub], 0, 0, 0);
+    }
+  }
+  bf16x8 pb[R];
+#pragma unroll
+  for (int rr = 0; rr < R; rr++) {
+    float x[8];
+#pragma unroll
+    for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+      for (int v = 0; v < 4; v++) x[4 * sub + v] = s[rr][sub][v] * scale_log2;
+    if (need_mask) {
+      // 32-bit visibility word of this stage for the lane's query: bit j <-> key key0 + j.
+      const uint32_t* arow = anc_lds + row_node[rr] * kAncWords;
+      const int np = S - key0;     // prefix keys in the stage (may be <= 0 or >= 32)
+      const int ne = kend - key0;  // keys before the split's end (>= 1)
+      uint32_t vis = np >= 32 ? 0xffffffffu : (np <= 0 ? 0u : ((1u << np) - 1u));
+      if (np < 32) {
+        uint32_t tree;
+        if (np > 0) {
+          tree = arow[0] << np;  // tree node 0 sits at bit np
+        } else {
+          const int t0 = -np, w0 = t0 >> 5, sh = t0 & 31;
+          const uint32_t lo = w0 < kAncWords ? arow[w0] : 0u;
+          const uint32_t hi = (w0 + 1 < kAncWords) ? arow[w0 + 1] : 0u;
+          tree = sh ? ((lo >> sh) | (hi << (32 - sh))) : lo;
+        }
+        vis |= tree;
+      }
+      if (ne < 32) vis &= (1u << ne) - 1u;  // keys past the split's end belong to the next split (or do not exist)
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const int j = 16 * (e >> 2) + 4 * kg + (e & 3);
+        x[e] = ((vis >> j) & 1u) ? x[e] : -INFINITY;
+      }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(st.m[rr], mx);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st.m[rr] - m_use);
+    float psum = 0.f;
+    union { bf16x8 v; uint16_t h[8]; } pk;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const float pe = __builtin_amdgcn_exp2f(x[e] - m_use);
+      psum += pe;
+      pk.h[e] = f2bf(pe);
+    }
+    pb[rr] = pk.v;
+    st.lsum[rr] = st.lsum[rr] * alpha + psum;
+    st.m[rr] = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 8; dt++) st.o[rr][dt] *= alpha;
+  }
+  // O^T += V^T P^T
+  const char* vbytes = reinterpret_cast<const char*>(vs);
+#pragma unroll
+  for (int dt = 0; dt < 8; dt++) {
+    bf16x4 va[2];
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      const int row = 16 * t + 4 * kg + (c >> 2);
+      const int piece = 2 * dt + ((c & 3) >> 1);
+      const int slot = piece ^ ((row & 7) << 1);
+      const char* addr = vbytes + row * 256 + slot * 16 + (c & 1) * 8;
+      va[t] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(addr));
+    }
+    const bf16x8 a = __builtin_shufflevector(va[0], va[1], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+    for (int rr = 0; rr < R; rr++)
+      st.o[rr][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rr], st.o[rr][dt], 0, 0, 0);
+  }
+}
+
+// grid: x = split, y = kv head + Hkv * row tile, z = sequence
+template <int R>
+__global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
+  CB_DECL_RING()
+  __shared__ int bt_lds[kMaxBtLds];
+  __shared__ uint32_t anc_lds[64 * R * kAncWords];
+  constexpr int D = 128;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  const int c = l & 15, kg = l >> 4;
+  const int b = blockIdx.z;
+  const int hk = blockIdx.y % p.Hkv, rt = blockIdx.y / p.Hkv;
+  const int g = p.Hq / p.Hkv;
+  const int off = meta.node_off[b];
+  const int N = meta.node_off[b + 1] - off;
+  const int S = meta.kv_len[b];
+  const int M = N * g;
+  const int row0 = rt * 64 * R;
+  if (row0 >= M) return;
+  const int len = S + N;
+  const int k0 = blockIdx.x * p.chunk;
+  if (k0 >= len) return;
+  const int k1 = (k0 + p.chunk < len) ? k0 + p.chunk : len;
+  const int nst = (k1 - k0 + kStageKeys - 1) / kStageKeys;
+  const int nsplit_b = (len + p.chunk - 1) / p.chunk;
+
+  KeyAddr ka;
+  ka.kv = &p.kv;
+  ka.bt = bt_lds;
+  ka.bt_first = 0;
+  ka.bs_shift = 0;
+  ka.seq = b;
+  ka.head = hk;
+  if (p.kv.block_size > 0) {  // the launcher guarantees a power-of-two block size and a slice that fits
+    ka.bs_shift = 31 - __clz(p.kv.block_size);
+    const int first = k0 >> ka.bs_shift, last = (k1 - 1) >> ka.bs_shift;
+    for (int i = tid; i <= last - first && i < kMaxBtLds; i += 256)
+      bt_lds[i] = p.kv.block_table[(int64_t)b * p.kv.max_blocks + first + i];
+    ka.bt_first = first;
+  }
+  const bool tree_split = k1 > S;  // this split reaches the tree nodes: masks needed
+  if (tree_split) {
+    for (int i = tid; i < 64 * R * kAncWords; i += 256) {
+      int row = row0 + i / kAncWords;
+      row = row < M ? row : M - 1;
+      anc_lds[i] = p.anc[(int64_t)(off + row / g) * kAncWords + (i % kAncWords)];
+    }
+  }
+  // this wave's rows: query c of row tile rr is row  row0 + (w*R + rr)*16 + c
+  WaveState<R> st;
+  int row_local[R];   // row index inside the workgroup's tile (for anc_lds)
+  int64_t grow[R];    // global output row (node * Hq + head), or -1 past the end
+#pragma unroll
+  for (int rr = 0; rr < R; rr++) {
+    const int rl = (w * R + rr) * 16 + c;
+    int row = row0 + rl;
+    const bool valid = row < M;
+    row = valid ? row : M - 1;
+    const int node = row / g, hg = row - node * g;
+    row_local[rr] = valid ? rl : (M - 1 - row0);
+    const int64_t gr = (int64_t)(off + node) * p.Hq + hk * g + hg;
+    grow[rr] = valid ? gr : -1;
+    const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.q) + gr * D);
+#pragma unroll
+    for (int ds = 0; ds < 4; ds++) st.q[rr][ds] = __builtin_bit_cast(bf16x8, qp[kg + 4 * ds]);
+#pragma unroll
+    for (int dt = 0; dt < 8; dt++) st.o[rr][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    st.m[rr] = -INFINITY;
+    st.lsum[rr] = 0.f;
+  }
+  __syncthreads();  // bt_lds / anc_lds visible
+
+  const char* kbase = reinterpret_cast<const char*>(p.kv.k);
+  const char* vbase = reinterpret_cast<const char*>(p.kv.v);
+  const float scale_log2 = p.scale * 1.4426950408889634f;
+  const int last_key = len - 1;
+
+#define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * kStageKeys, last_key, w, l)
+  // prologue: NS-1 stages in flight
+  if (0 < nst) CB_ISSUE(0, 0);
+  if (1 < nst) CB_ISSUE(1, 1);
+  if (2 < nst) CB_ISSUE(2, 2);
+
+#define CB_STAGE(J, JPREV)                                                                         \
+  {                                                                                                \
+    const int s = s0 + J;                                                                          \
+    if (s < nst) {                                                                                 \
+      const int after = nst - 1 - s; /* stages issued after this one, at most NS-2 */             \
+      if (after >= 2) wait_vmcnt<8>(); else if (after == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); \
+      ring_barrier();                                                                              \
+      if (s + NS - 1 < nst) CB_ISSUE(JPREV, s + NS - 1);                                           \
+      const int key0 = k0 + s * kStageKeys;                                                        \
+      const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                      \
+      compute_stage<R>(K##J, V##J, st, scale_log2, key0, S, k1, need_mask, anc_lds, row_local, l); \
+    }                                                                                              \
+  }
+  for (int s0 = 0; s0 < nst; s0 += NS) {
+    CB_STAGE(0, 3)
+    CB_STAGE(1, 0)
+    CB_STAGE(2, 1)
+    CB_STAGE(3, 2)
+  }
+#undef CB_STAGE
+#undef CB_ISSUE
+
+  // finish: the denominator is spread over the 4 lanes that share a query
+#pragma unroll
+  for (int rr = 0; rr < R; rr++) {
+    float lt = st.lsum[rr];
+    lt += __shfl_xor(lt, 16, 64);
+    lt += __shfl_xor(lt, 32, 64);
+    if (grow[rr] < 0) continue;
+    if (nsplit_b == 1) {
+      const float inv = 1.0f / lt;
+      uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + grow[rr] * D;
+#pragma unroll
+      for (int dt = 0; dt < 8; dt++) {
+        uint2 pk;
+        pk.x = (uint32_t)f2bf(st.o[rr][dt][0] * inv) | ((uint32_t)f2bf(st.o[rr][dt][1] * inv) << 16);
+        pk.y = (uint32_t)f2bf(st.o[rr][dt][2] * inv) | ((uint32_t)f2bf(st.o[rr][dt][3] * inv) << 16);
+        *reinterpret_cast<uint2*>(orow + 16 * dt + 4 * kg) = pk;
+      }
+    } else {
+      float* pr = p.partial + (grow[rr] * p.nsplit + blockIdx.x) * (D + 2);
+#pragma unroll
+      for (int dt = 0; dt < 8; dt++) {
+        float2* dst = reinterpret_cast<float2*>(pr + 16 * dt + 4 * kg);  // rows are 8-byte aligned only
+        dst[0] = float2{st.o[rr][dt][0], st.o[rr][dt][1]};
+        dst[1] = float2{st.o[rr][dt][2], st.o[rr][dt][3]};
+      }
+      if (kg == 0) {
+        pr[D] = st.m[rr] * 0.6931471805599453f;  // back to the natural-log domain used by the merge
+        pr[D + 1] = lt;
+      }
+    }
+  }
+}
+
+bool attn_mfma_supports(const AttnParams& p) {
+  if (p.D != 128) return false;
+  if (p.kv.block_size > 0) {
+    if (p.kv.block_size & (p.kv.block_size - 1)) return false;
+    if (p.chunk / p.kv.block_size + 2 > kMaxBtLds) return false;
+  }
+  return true;
+}
+
+hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call) {
+  if (!attn_mfma_supports(p)) return hipErrorInvalidValue;
+  const int g = p.Hq / p.Hkv;
+  const int M = max_nodes_in_call * g;
+  const int R = M <= 64 ? 1 : (M <= 128 ? 2 : 4);
+  const int tiles = (M + 64 * R - 1) / (64 * R);
+  dim3 grid(p.nsplit, p.Hkv * tiles, p.batch);
+  if (R == 1) hipLaunchKernelGGL(k_attn_mfma<1>, grid, dim3(256), 0, st, p, meta);
+  else if (R == 2) hipLaunchKernelGGL(k_attn_mfma<2>, grid, dim3(256), 0, st, p, meta);
+  else hipLaunchKernelGGL(k_attn_mfma<4>, grid, dim3(256), 0, st, p, meta);
+  return hipGetLastError();
+}
+
 }  // namespace cb

@@ -75,7 +75,7 @@ hipError_t launch_compact(hipStream_t st, int batch, const SeqMeta& meta, const 
 hipError_t launch_attn_simt(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype,
                             int max_nodes_in_call);
 hipError_t launch_merge(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype, int total_nodes);
-hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
-                            int max_len_in_call);
+bool attn_mfma_supports(const AttnParams& p);  // shape/geometry the MFMA kernel takes (bf16 is the caller's check)
+hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call);
 
 }  // namespace cb
