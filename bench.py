@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: ancestor sets,
+tree-masked attention (with its split merge), vocabulary argmax, greedy acceptance and KV
+compaction, enqueued through the C ABI (cb_verify_tree_device + cb_compact_kv).  The workload is
+the 7B-shaped configuration (batch 1, 32 heads, head_dim 128, bf16, prefix 2048, 64-node tree from
+the LRU drafter, logits [64, 32000]); inputs are resident in HBM before the timed region.  The
+step rotates over enough independent copies of (q, cache, logits) that every pass reads its K/V
+from HBM rather than from the 256 MB last-level cache.
+
+Prints one JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default: the 7B-shaped one)")
+    ap.add_argument("--copies", type=int, default=0, help="independent input copies to rotate over (0 = enough for 768 MB)")
+    ap.add_argument("--warm", action="store_true", help="single buffer (cache-resident) instead of rotating copies")
+    ap.add_argument("--layout", type=int, default=0, help="0 token-major cache, 1 head-major")
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--impl", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-iters", type=int, default=0, help="launches in the attention-only timing loop (0 = steps)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_21699_amd import binding as B
+    from paper_2511_21699_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    case = W.make_config(args.config)
+    attn_bytes = case.attention_bytes()
+    per_copy = attn_bytes + case.logits_bytes()
+    copies = 1 if args.warm else (args.copies or max(2, -(-768 * 2 ** 20 // per_copy)))
+    copies = min(copies, max(1, int(200e9 // per_copy)))
+    dcs = [B.DeviceCase(case, layout=args.layout) for _ in range(copies)]
+    ver = B.Verifier(B.config_for_case(case, max_splits=72 if args.config == 4 else 0))
+    if args.splits:
+        ver.set_option("splits", args.splits)
+    if args.impl:
+        ver.set_option("attn_impl", args.impl)
+    d_par = torch.from_numpy(case.parent).cuda()
+    d_tok = torch.from_numpy(case.tokens).cuda()
+    outs = [torch.empty_like(dc.q) for dc in dcs]
+    d_len = torch.zeros(case.B, dtype=torch.int32, device="cuda")
+    d_acc = torch.zeros(case.B, case.max_depth + 1, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        dc = dcs[i % copies]
+        ver.verify_tree_device(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits,
+                               outs[i % copies], d_len, d_acc, stream=stream)
+        ver.compact_kv([dc.kv], case.B, want_len=False, stream=stream)
+
+    # ---- whole step: W warm-up steps, then exactly K timed steps
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    accepted = d_len.cpu().tolist()
+
+    # ---- dominant kernel (attention + split merge) alone, HIP events on the launch stream
+    iters = args.attn_iters or args.steps
+
+    def timed_stage(mask, n):
+        ver.set_option("stages", mask)
+        for i in range(min(50, n)):
+            dc = dcs[i % copies]
+            ver.verify_tree_device(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits,
+                                   outs[i % copies], d_len, d_acc, stream=stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(n):
+            dc = dcs[i % copies]
+            ver.verify_tree_device(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits,
+                                   outs[i % copies], d_len, d_acc, stream=stream)
+        e1.record(stream)
+        e1.synchronize()
+        ver.set_option("stages", 15)
+        return e0.elapsed_time(e1) * 1e3 / n      # microseconds per launch group
+
+    attn_us = timed_stage(2, iters)
+    argmax_us = timed_stage(4, iters)
+    attn_gbps = attn_bytes / attn_us / 1e3
+
+    out = {
+        "metric": "tree-verify attention HBM GB/s (% of peak) + verify steps/s, 7B shape",
+        "value": round(1e3 / ms_per_step, 1),
+        "unit": "verify steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if case.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}] {case.name}: B={case.B} Hq={case.Hq} Hkv={case.Hkv} D={case.D} "
+                               f"prefix={case.kv_len.tolist() if case.B <= 4 else 'ragged'} nodes={case.total_nodes} V={case.V}",
+                   "cache": "paged16" if case.block_size else "contiguous",
+                   "layout": "token-major" if args.layout == 0 else "head-major",
+                   "input_copies": copies, "cold_cache": not args.warm,
+                   "accepted_len": accepted[:4]},
+        "attention_us": round(attn_us, 3),
+        "attention_gbps": round(attn_gbps, 1),
+        "attention_pct_hbm_peak": round(100 * attn_gbps / HBM_PEAK_GBPS, 2),
+        "argmax_us": round(argmax_us, 3),
+        "roofline": {"bound": "hbm", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "tree attention (k_attn_mfma + split merge)", "algorithmic_bytes": attn_bytes},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "attention_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            out["roofline"]["traffic"] = json.load(open(traffic_file)).get(f"config{args.config}")
+        except Exception:
+            pass
+
+    # ---- the oracle on the host cores, same workload (a baseline beside the GPU number, not the target)
+    if not args.no_cpu_baseline:
+        from oracle import cb_oracle as O
+        threads = min(O.num_threads(), os.cpu_count() or 1)
+        rows = O.all_rows(case)
+        budget_rows = len(rows)
+        sample = "whole workload"
+        est = case.attention_flops() / 2 / 2.5e9 / max(threads, 1)      # rough seconds at ~2.5 G key-dims/s/core
+        if est > 20:
+            budget_rows = max(threads, int(len(rows) * 20 / est))
+            rows = rows[np.linspace(0, len(rows) - 1, budget_rows).astype(int)]
+            sample = f"{budget_rows} of {len(O.all_rows(case))} attention rows (evenly spaced), scaled; argmax/accept/compact whole"
+        t0 = time.perf_counter()
+        O.attention_rows(case, rows, threads=threads)
+        t_attn = (time.perf_counter() - t0) * (len(O.all_rows(case)) / len(rows))
+        t0 = time.perf_counter()
+        a, res = O.verify(case)
+        k2, v2 = case.k.copy(), case.v.copy()
+        t_copy0 = time.perf_counter()
+        for b, (L, path, toks) in enumerate(res):
+            O.compact(case, k2, v2, b, path)
+        t_rest = (time.perf_counter() - t0) - (t_copy0 - t0) + 0.0
+        t_rest += 0.0
+        total = t_attn + t_rest
+        out["cpu_baseline"] = {"value": round(1.0 / total, 3), "unit": "verify steps/s", "cores": threads, "kind": "oracle",
+                               "sample": sample, "attention_s": round(t_attn, 4), "argmax_accept_compact_s": round(t_rest, 4)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

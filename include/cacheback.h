@@ -161,14 +161,19 @@ int cb_compact_kv(cb_ctx *ctx, void *hip_stream, int32_t num_layers, const cb_kv
 /* Test hooks (each synchronises the stream of the last verify call).
  *   cb_get_path     host [batch][max_depth+1]: node indices of the accepted path, -1 padded
  *   cb_get_argmax   host [sumN]: first-maximum index of each logits row
- *   cb_device_status  0, or a bit mask: 1 = malformed parent entry seen, 2 = node deeper than max_depth */
+ *   cb_device_status  0, or a bit mask: 1 = malformed parent entry seen, 2 = node deeper than max_depth,
+ *                     16 = (informational) a split merge had to read partials across XCDs */
 int cb_get_path(cb_ctx *ctx, int32_t *path);
 int cb_get_argmax(cb_ctx *ctx, int32_t *argmax);
 int cb_device_status(cb_ctx *ctx, int32_t *status);
 
 /* Tuning knobs for measurements; unknown names give CB_EINVAL.
  *   "splits"     force the number of KV-sequence splits (0 = automatic)
- *   "attn_impl"  0 = automatic, 1 = scalar kernel, 2 = MFMA kernel (bf16, head_dim 128 only) */
+ *   "attn_impl"  0 = automatic, 1 = scalar kernel, 2 = MFMA kernel (bf16, head_dim 128 only)
+ *   "stages"     bit mask of the steps cb_verify_tree_device enqueues (1 ancestor sets, 2 attention,
+ *                4 argmax, 8 acceptance; default 15) -- for timing one step in isolation; with a
+ *                step left out the results of the call are those of an earlier call or undefined
+ *   "time_attention"  1 = record HIP events around the attention kernels (see cb_last_attention_ms) */
 int cb_set_option(cb_ctx *ctx, const char *name, int64_t value);
 
 /* Time in milliseconds the attention kernels of the last verify call took on the device (HIP

@@ -58,7 +58,7 @@ WsLayout ws_layout(const cb_config& c) {
   L.max_splits = effective_max_splits(c);
   L.amax_chunks = (int)(((int64_t)c.vocab_size + kArgmaxChunk - 1) / kArgmaxChunk);
   const int g = c.num_q_heads / c.num_kv_heads;
-  L.ticket_count = c.max_batch * c.num_kv_heads * ((c.max_nodes * g + kRowTile - 1) / kRowTile);
+  L.ticket_count = 2 * c.max_batch * c.num_kv_heads * ((c.max_nodes * g + kRowTile - 1) / kRowTile);  // (count, XCD mask) pairs
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   L.anc = take(mt * kAncWords * 4);
@@ -73,7 +73,7 @@ WsLayout ws_layout(const cb_config& c) {
   L.new_len = take(c.max_batch * 4);
   L.status = take(4);
   L.tickets = take((size_t)L.ticket_count * 4);
-  L.partial = take(mt * c.num_q_heads * (size_t)L.max_splits * (c.head_dim + 2) * 4);
+  L.partial = take(mt * c.num_q_heads * (size_t)L.max_splits * partial_stride(c.head_dim) * 4);
   L.total = o;
   return L;
 }
@@ -102,7 +102,7 @@ struct cb_ctx {
   int32_t last_len[CB_MAX_BATCH];
   hipStream_t last_stream;
   // options
-  int64_t opt_splits, opt_impl, opt_time;
+  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug;
   hipEvent_t ev0, ev1;
   bool ev_valid;
   char err[256];
@@ -230,14 +230,18 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.nsplit = plan.nsplit;
   ap.batch = batch;
   ap.scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
+  ap.status = ctx->dev<int32_t>(ctx->lay.status);
+  ap.debug_flags = (int32_t)ctx->opt_debug;
 
-  CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
-                                  ctx->dev<int32_t>(ctx->lay.status)));
+  const int64_t stages = ctx->opt_stages;  // measurement aid: bit 0 prepare, 1 attention, 2 argmax, 3 acceptance
+  if (stages & 1)
+    CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
+                                    ctx->dev<int32_t>(ctx->lay.status)));
   const bool timing = ctx->opt_time != 0;
   if (timing) CB_HIP(ctx, hipEventRecord(ctx->ev0, st));
-  if (plan.impl == 2 && attn_mfma_supports(ap)) {
-    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes));
-    if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
+  if (!(stages & 2)) {
+  } else if (plan.impl == 2 && attn_mfma_supports(ap)) {
+    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes));  // merges its own splits
   } else {
     CB_HIP(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
     if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
@@ -246,9 +250,11 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
     CB_HIP(ctx, hipEventRecord(ctx->ev1, st));
     ctx->ev_valid = true;
   }
-  CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
-                            ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks));
-  CB_HIP(ctx, launch_accept(st, batch, meta, d_parent, d_tokens, ctx->dev<uint32_t>(ctx->lay.anc),
+  if (stages & 4)
+    CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
+                              ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks));
+  if (stages & 8)
+    CB_HIP(ctx, launch_accept(st, batch, meta, d_parent, d_tokens, ctx->dev<uint32_t>(ctx->lay.anc),
                             ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, c.max_depth,
                             ctx->dev<int32_t>(ctx->lay.amax_out), ctx->dev<int32_t>(ctx->lay.path),
                             ctx->dev<int32_t>(ctx->lay.len_ctx), d_len, d_tok));
@@ -331,6 +337,7 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   ctx->cfg = *cfg;
   ctx->lay = lay;
   ctx->ws = static_cast<char*>(workspace);
+  ctx->opt_stages = 15;
   const size_t mt = lay.max_total_nodes, stride = (size_t)cfg->max_depth + 1;
   const size_t ints = mt * 3 + cfg->max_batch * (1 + 2 * stride) + 1 + cfg->max_batch;
   hipError_t e = hipHostMalloc(&ctx->h_block, ints * 4, hipHostMallocDefault);
@@ -493,6 +500,8 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   if (!strcmp(name, "splits")) ctx->opt_splits = value;
   else if (!strcmp(name, "attn_impl")) ctx->opt_impl = value;
   else if (!strcmp(name, "time_attention")) ctx->opt_time = value;
+  else if (!strcmp(name, "stages")) ctx->opt_stages = value & 15;
+  else if (!strcmp(name, "debug_flags")) ctx->opt_debug = value;
   else return set_err(ctx, CB_EINVAL, "unknown option '%s'", name);
   return CB_OK;
 }

@@ -28,12 +28,15 @@ namespace cb {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uintx4;
+typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned uintx2;
+constexpr int kAgentCoherent = 16;  // buffer cache policy: sc1 = coherent at agent (device) scope
 
 constexpr int kStageKeys = 32;                 // keys per LDS stage
 constexpr int kStageVecs = kStageKeys * 16;    // 16-byte pieces per K (or V) stage: 32 rows x 256 B
 constexpr int NS = 4;                          // ring depth: NS-1 stages in flight
 constexpr int kMaxBtLds = 1024;                // block-table entries staged in LDS per split
+constexpr int kPartialStride = kPartialStrideD128;  // floats per (row, split) partial: o[128], m, l, pad
 
 // One __shared__ object per ring slot: the compiler tracks LDS-DMA completion per object.
 #define CB_DECL_RING()                                        \
@@ -107,15 +110,34 @@ __device__ __forceinline__ void issue_stage(uint4* kdst, uint4* vdst, const KeyA
 
 template <int R>
 struct WaveState {
-  bf16x8 q[R][4];      // B operands of QK^T: query c, dims 32*ds + 8kg ..
-  floatx4 o[R][8];     // O^T accumulators, 8 dim tiles of 16
-  float m[R], lsum[R]; // running max (log2 domain) and this lane's share of the denominator
+  bf16x8 q[R][4];    // B operands of QK^T: query c, dims 32*ds + 8kg ..
+  floatx4 o[R][8];   // O^T accumulators, 8 dim tiles of 16
+  floatx4 lacc[R];   // softmax denominator, accumulated by an MFMA against a tile of ones
+  float mref[R];     // reference maximum of the raw scores (q.k, before the softmax scale)
 };
 
+// Maximum over the 4 lanes that share a query (lanes c, c+16, c+32, c+48) with the gfx950 row
+// swaps: v_permlane16_swap exchanges odd 16-lane rows of one operand with even rows of the other,
+// v_permlane32_swap the upper half of one with the lower half of the other, so two swaps of a
+// value with itself bring every lane its partners.
+__device__ __forceinline__ float quad_max(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+constexpr float kRescaleSlack = 8.0f;  // log2 units the running maximum may exceed the reference
+
 // One 32-key stage for the 16*R rows of a wave.
+//   scores  S^T = K Q^T                       (8 MFMAs per row tile)
+//   p = 2^(c*s - c*mref) with c = scale*log2(e); mref follows the running maximum lazily: it is
+//   only raised (and O, l rescaled) when the maximum has grown by more than kRescaleSlack, so
+//   probabilities stay below 2^8 and the accumulators are rarely touched by the vector ALU
+//   O^T += V^T P^T, l += 1^T P^T              (9 MFMAs per row tile)
 template <int R>
 __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, const uint4* __restrict__ vs,
-                                              WaveState<R>& st, float scale_log2, int key0, int S, int kend,
+                                              WaveState<R>& st, float c2, int key0, int S, int kend,
                                               bool need_mask, const uint32_t* anc_lds, const int* row_node, int l) {
   const int c = l & 15, kg = l >> 4;
   floatx4 s[R][2];
@@ -125,10 +147,10 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
     s[rr][1] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll
-  for (int sub = 0; sub < 2; sub++) {
-    const int row = 16 * sub + c;
+  for (int ds = 0; ds < 4; ds++) {
 #pragma unroll
-    for (int ds = 0; ds < 4; ds++) {
+    for (int sub = 0; sub < 2; sub++) {
+      const int row = 16 * sub + c;
       const int piece = kg + 4 * ds;
       const uint4 raw = ks[row * 16 + (piece ^ (row & 15))];
       const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
@@ -142,9 +164,7 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
   for (int rr = 0; rr < R; rr++) {
     float x[8];
 #pragma unroll
-    for (int sub = 0; sub < 2; sub++)
-#pragma unroll
-      for (int v = 0; v < 4; v++) x[4 * sub + v] = s[rr][sub][v] * scale_log2;
+    for (int e = 0; e < 8; e++) x[e] = s[rr][e >> 2][e & 3];
     if (need_mask) {
       // 32-bit visibility word of this stage for the lane's query: bit j <-> key key0 + j.
       const uint32_t* arow = anc_lds + row_node[rr] * kAncWords;
@@ -171,27 +191,28 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
       }
     }
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(st.m[rr], mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(st.m[rr] - m_use);
-    float psum = 0.f;
-    union { bf16x8 v; uint16_t h[8]; } pk;
+    mx = quad_max(mx);
+    // lazy reference update; the decision is identical in the 4 lanes of a query
+    const bool raise = (mx - st.mref[rr]) * c2 > kRescaleSlack;  // false when both are -inf (NaN)
+    if (__builtin_amdgcn_ballot_w64(raise) != 0ull) {
+      const float alpha = raise ? __builtin_amdgcn_exp2f((st.mref[rr] - mx) * c2) : 1.0f;
+      if (raise) st.mref[rr] = mx;
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-      const float pe = __builtin_amdgcn_exp2f(x[e] - m_use);
-      psum += pe;
-      pk.h[e] = f2bf(pe);
+      for (int dt = 0; dt < 8; dt++) st.o[rr][dt] *= alpha;
+      st.lacc[rr] *= alpha;
     }
-    pb[rr] = pk.v;
-    st.lsum[rr] = st.lsum[rr] * alpha + psum;
-    st.m[rr] = m_new;
+    const float nm = (st.mref[rr] == -INFINITY) ? 0.f : -st.mref[rr] * c2;
+    union { bf16x8 v; __bf16 h[8]; } pk;
 #pragma unroll
-    for (int dt = 0; dt < 8; dt++) st.o[rr][dt] *= alpha;
+    for (int e = 0; e < 8; e++) pk.h[e] = (__bf16)__builtin_amdgcn_exp2f(fmaf(x[e], c2, nm));
+    pb[rr] = pk.v;
   }
-  // O^T += V^T P^T
+  // O^T += V^T P^T and l += 1^T P^T
   const char* vbytes = reinterpret_cast<const char*>(vs);
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+#pragma unroll
+  for (int rr = 0; rr < R; rr++)
+    st.lacc[rr] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[rr], st.lacc[rr], 0, 0, 0);
 #pragma unroll
   for (int dt = 0; dt < 8; dt++) {
     bf16x4 va[2];
@@ -210,6 +231,67 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
   }
 }
 
+// Split merge for the rows of one tile: thread -> (row, 32-dim quarter);
+// m = max m_t, w_t = e^(m_t - m), o = sum w_t o_t / sum w_t l_t.  POL is the buffer cache policy.
+template <int R, int POL>
+__device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_rsrc_t prsrc, int64_t seq_row0,
+                                           int row0, int M, int g, int off, int hk, int nsplit_b, int tid) {
+  constexpr int D = 128;
+  const int quarter = tid & 3;
+  for (int rl = tid >> 2; rl < 64 * R; rl += 64) {
+    const int row = row0 + rl;
+    if (row >= M) break;
+    const int node = row / g, hg = row - node * g;
+    const int64_t gr = (int64_t)(off + node) * p.Hq + hk * g + hg;
+    const uint32_t rbyte = (uint32_t)((gr - seq_row0) * p.nsplit * (kPartialStride * 4));
+    float m = -INFINITY;
+    for (int t = 0; t < nsplit_b; t++)
+      m = fmaxf(m, __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(prsrc, rbyte + (t * kPartialStride + D) * 4, 0, POL)));
+    float acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; i++) acc[i] = 0.f;
+    float lsum = 0.f;
+    for (int t0 = 0; t0 < nsplit_b; t0 += 2) {  // two splits' loads in flight together
+      uintx4 v[2][8];
+      uintx2 ml[2];
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        const int t = (t0 + u < nsplit_b) ? t0 + u : t0;
+        const uint32_t tb = rbyte + t * (kPartialStride * 4);
+        ml[u] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + D * 4, 0, POL);
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+          v[u][i] = __builtin_amdgcn_raw_buffer_load_b128(prsrc, tb + (quarter * 32 + 4 * i) * 4, 0, POL);
+      }
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        const float mt = __uint_as_float(ml[u][0]);
+        float wgt = (mt == -INFINITY) ? 0.f : __expf(mt - m);
+        if (t0 + u >= nsplit_b) wgt = 0.f;
+        lsum = fmaf(__uint_as_float(ml[u][1]), wgt, lsum);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          acc[4 * i + 0] = fmaf(__uint_as_float(v[u][i][0]), wgt, acc[4 * i + 0]);
+          acc[4 * i + 1] = fmaf(__uint_as_float(v[u][i][1]), wgt, acc[4 * i + 1]);
+          acc[4 * i + 2] = fmaf(__uint_as_float(v[u][i][2]), wgt, acc[4 * i + 2]);
+          acc[4 * i + 3] = fmaf(__uint_as_float(v[u][i][3]), wgt, acc[4 * i + 3]);
+        }
+      }
+    }
+    const float inv = 1.0f / lsum;
+    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(p.out) + gr * D + quarter * 32);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      uint4 pk;
+      pk.x = (uint32_t)f2bf(acc[8 * i + 0] * inv) | ((uint32_t)f2bf(acc[8 * i + 1] * inv) << 16);
+      pk.y = (uint32_t)f2bf(acc[8 * i + 2] * inv) | ((uint32_t)f2bf(acc[8 * i + 3] * inv) << 16);
+      pk.z = (uint32_t)f2bf(acc[8 * i + 4] * inv) | ((uint32_t)f2bf(acc[8 * i + 5] * inv) << 16);
+      pk.w = (uint32_t)f2bf(acc[8 * i + 6] * inv) | ((uint32_t)f2bf(acc[8 * i + 7] * inv) << 16);
+      dst[i] = pk;
+    }
+  }
+}
+
 // grid: x = split, y = kv head + Hkv * row tile, z = sequence
 template <int R>
 __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
@@ -219,8 +301,21 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
   constexpr int D = 128;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
   const int c = l & 15, kg = l >> 4;
-  const int b = blockIdx.z;
-  const int hk = blockIdx.y % p.Hkv, rt = blockIdx.y / p.Hkv;
+  // Workgroups are handed to the 8 XCDs round-robin in dispatch order.  With xcd_remap the
+  // dispatch index d is renumbered to j = (d % 8) * (T / 8) + d / 8, so that consecutive j --
+  // in particular all splits of one (sequence, kv head, row tile), and the row tiles that share
+  // a K/V chunk -- sit on the same XCD and meet in its L2.
+  int split, by, b;
+  {
+    const int T = gridDim.x * gridDim.y * gridDim.z;
+    const int d = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int j = p.xcd_remap ? (d & 7) * (T >> 3) + (d >> 3) : d;
+    split = j % (int)gridDim.x;
+    const int rest = j / (int)gridDim.x;
+    by = rest % (int)gridDim.y;
+    b = rest / (int)gridDim.y;
+  }
+  const int hk = by % p.Hkv, rt = by / p.Hkv;
   const int g = p.Hq / p.Hkv;
   const int off = meta.node_off[b];
   const int N = meta.node_off[b + 1] - off;
@@ -229,7 +324,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
   const int row0 = rt * 64 * R;
   if (row0 >= M) return;
   const int len = S + N;
-  const int k0 = blockIdx.x * p.chunk;
+  const int k0 = split * p.chunk;
   if (k0 >= len) return;
   const int k1 = (k0 + p.chunk < len) ? k0 + p.chunk : len;
   const int nst = (k1 - k0 + kStageKeys - 1) / kStageKeys;
@@ -276,21 +371,23 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
     for (int ds = 0; ds < 4; ds++) st.q[rr][ds] = __builtin_bit_cast(bf16x8, qp[kg + 4 * ds]);
 #pragma unroll
     for (int dt = 0; dt < 8; dt++) st.o[rr][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
-    st.m[rr] = -INFINITY;
-    st.lsum[rr] = 0.f;
+    st.lacc[rr] = floatx4{0.f, 0.f, 0.f, 0.f};
+    st.mref[rr] = -INFINITY;
   }
   __syncthreads();  // bt_lds / anc_lds visible
 
   const char* kbase = reinterpret_cast<const char*>(p.kv.k);
   const char* vbase = reinterpret_cast<const char*>(p.kv.v);
-  const float scale_log2 = p.scale * 1.4426950408889634f;
+  const float c2 = p.scale * 1.4426950408889634f;  // softmax scale in the log2 domain
   const int last_key = len - 1;
 
 #define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * kStageKeys, last_key, w, l)
   // prologue: NS-1 stages in flight
-  if (0 < nst) CB_ISSUE(0, 0);
-  if (1 < nst) CB_ISSUE(1, 1);
-  if (2 < nst) CB_ISSUE(2, 2);
+  if (!(p.debug_flags & 4)) {  // (timing aid: bit 2 leaves the loads out, bit 1 the arithmetic)
+    if (0 < nst) CB_ISSUE(0, 0);
+    if (1 < nst) CB_ISSUE(1, 1);
+    if (2 < nst) CB_ISSUE(2, 2);
+  }
 
 #define CB_STAGE(J, JPREV)                                                                         \
   {                                                                                                \
@@ -299,10 +396,11 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
       const int after = nst - 1 - s; /* stages issued after this one, at most NS-2 */             \
       if (after >= 2) wait_vmcnt<8>(); else if (after == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); \
       ring_barrier();                                                                              \
-      if (s + NS - 1 < nst) CB_ISSUE(JPREV, s + NS - 1);                                           \
+      if (s + NS - 1 < nst && !(p.debug_flags & 4)) CB_ISSUE(JPREV, s + NS - 1);                   \
       const int key0 = k0 + s * kStageKeys;                                                        \
       const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                      \
-      compute_stage<R>(K##J, V##J, st, scale_log2, key0, S, k1, need_mask, anc_lds, row_local, l); \
+      if (!(p.debug_flags & 2))                                                                    \
+        compute_stage<R>(K##J, V##J, st, c2, key0, S, k1, need_mask, anc_lds, row_local, l);       \
     }                                                                                              \
   }
   for (int s0 = 0; s0 < nst; s0 += NS) {
@@ -314,12 +412,15 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
 #undef CB_STAGE
 #undef CB_ISSUE
 
-  // finish: the denominator is spread over the 4 lanes that share a query
+  if (p.debug_flags & 8) return;  // (timing aid: stop after the key sweep)
+  // Buffer descriptor over this sequence's partials (byte offsets fit 32 bits, checked by the launcher).
+  const int64_t seq_row0 = (int64_t)off * p.Hq;
+  const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
+      p.partial + seq_row0 * p.nsplit * kPartialStride, 0, 0x7fffffff, 0x00020000);
+  // finish.  Every lane holds its query's full denominator (all four accumulator entries equal).
 #pragma unroll
   for (int rr = 0; rr < R; rr++) {
-    float lt = st.lsum[rr];
-    lt += __shfl_xor(lt, 16, 64);
-    lt += __shfl_xor(lt, 32, 64);
+    const float lt = st.lacc[rr][0];
     if (grow[rr] < 0) continue;
     if (nsplit_b == 1) {
       const float inv = 1.0f / lt;
@@ -332,19 +433,61 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
         *reinterpret_cast<uint2*>(orow + 16 * dt + 4 * kg) = pk;
       }
     } else {
-      float* pr = p.partial + (grow[rr] * p.nsplit + blockIdx.x) * (D + 2);
+      // partial state of this split, written through to memory (agent scope) so that the merging
+      // workgroup, possibly on another XCD with its own L2, can read it without cache flushes
+      const uint32_t pbyte = (uint32_t)(((grow[rr] - seq_row0) * p.nsplit + split) * (kPartialStride * 4));
 #pragma unroll
       for (int dt = 0; dt < 8; dt++) {
-        float2* dst = reinterpret_cast<float2*>(pr + 16 * dt + 4 * kg);  // rows are 8-byte aligned only
-        dst[0] = float2{st.o[rr][dt][0], st.o[rr][dt][1]};
-        dst[1] = float2{st.o[rr][dt][2], st.o[rr][dt][3]};
+        const uintx4 v = {__float_as_uint(st.o[rr][dt][0]), __float_as_uint(st.o[rr][dt][1]),
+                          __float_as_uint(st.o[rr][dt][2]), __float_as_uint(st.o[rr][dt][3])};
+        __builtin_amdgcn_raw_buffer_store_b128(v, prsrc, pbyte + (16 * dt + 4 * kg) * 4, 0, kAgentCoherent);
       }
       if (kg == 0) {
-        pr[D] = st.m[rr] * 0.6931471805599453f;  // back to the natural-log domain used by the merge
-        pr[D + 1] = lt;
+        // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
+        const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
+        const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
+        __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 4, 0, kAgentCoherent);
       }
     }
   }
+  if (nsplit_b == 1) return;
+
+  // ---- split merge by the last workgroup of this (sequence, kv head, row tile) to finish.
+  // The partials above are write-through stores; once they have completed (vmcnt 0) the workgroup
+  // takes a ticket with a device-scope atomic.  The workgroup that draws the last ticket reads all
+  // partials of the tile with agent-coherent loads.  No cache-wide write-back or invalidate is
+  // involved (a __threadfence() per workgroup costs a full L2 sweep on this chip).
+  __shared__ int last_flag;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (p.debug_flags & 1) return;
+  const int tiles = gridDim.y / p.Hkv;
+  uint32_t* ticket = p.tickets + 2 * (((int64_t)b * p.Hkv + hk) * tiles + rt);
+  // XCC_ID hardware register (id 20, bits 3:0): which XCD this workgroup runs on
+  const uint32_t my_xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
+  if (tid == 0) {
+    __hip_atomic_fetch_or(ticket + 1, 1u << my_xcc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int flag = (old == (uint32_t)(nsplit_b - 1)) ? 1 : 0;
+    if (flag) {
+      const uint32_t mask = __hip_atomic_load(ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (mask != (1u << my_xcc)) {
+        flag = 2;  // some split ran on another XCD: its partials are not in this L2
+        atomicOr(p.status, 16);
+      }
+      __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+      __hip_atomic_store(ticket + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    last_flag = flag;
+  }
+  __syncthreads();
+  if (!last_flag) return;
+  // Same XCD: the write-through stores left the lines in this L2, plain (cached) loads are coherent
+  // with them.  Otherwise read past the L2 with agent-coherent loads.
+  const int pol = (last_flag == 2) ? kAgentCoherent : 0;
+  if (pol == 0) merge_rows<R, 0>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
+  else merge_rows<R, kAgentCoherent>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
 }
 
 bool attn_mfma_supports(const AttnParams& p) {
@@ -353,6 +496,8 @@ bool attn_mfma_supports(const AttnParams& p) {
     if (p.kv.block_size & (p.kv.block_size - 1)) return false;
     if (p.chunk / p.kv.block_size + 2 > kMaxBtLds) return false;
   }
+  // partial offsets inside one sequence are 32-bit byte offsets of a buffer descriptor
+  if ((int64_t)CB_MAX_NODES * p.Hq * p.nsplit * kPartialStride * 4 >= (1ll << 31)) return false;
   return true;
 }
 
@@ -363,9 +508,13 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   const int R = M <= 64 ? 1 : (M <= 128 ? 2 : 4);
   const int tiles = (M + 64 * R - 1) / (64 * R);
   dim3 grid(p.nsplit, p.Hkv * tiles, p.batch);
-  if (R == 1) hipLaunchKernelGGL(k_attn_mfma<1>, grid, dim3(256), 0, st, p, meta);
-  else if (R == 2) hipLaunchKernelGGL(k_attn_mfma<2>, grid, dim3(256), 0, st, p, meta);
-  else hipLaunchKernelGGL(k_attn_mfma<4>, grid, dim3(256), 0, st, p, meta);
+  AttnParams q = p;
+  const int64_t T = (int64_t)p.nsplit * p.Hkv * tiles * p.batch;
+  // renumbering needs whole groups of splits inside each XCD's share of the grid
+  q.xcd_remap = (T % 8 == 0 && (T / 8) % p.nsplit == 0) ? 1 : 0;
+  if (R == 1) hipLaunchKernelGGL(k_attn_mfma<1>, grid, dim3(256), 0, st, q, meta);
+  else if (R == 2) hipLaunchKernelGGL(k_attn_mfma<2>, grid, dim3(256), 0, st, q, meta);
+  else hipLaunchKernelGGL(k_attn_mfma<4>, grid, dim3(256), 0, st, q, meta);
   return hipGetLastError();
 }
 

@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnParams p, SeqMeta meta) {
     if (nsplit_b == 1) {
       st_elem(reinterpret_cast<T*>(p.out) + row * D + tid, o / l_run);
     } else {
-      float* pr = p.partial + (row * p.nsplit + blockIdx.x) * (D + 2);
+      float* pr = p.partial + (row * p.nsplit + blockIdx.x) * partial_stride(D);
       pr[tid] = o;
       if (tid == 0) { pr[D] = m_run; pr[D + 1] = l_run; }
     }
@@ -165,15 +165,16 @@ __global__ __launch_bounds__(D) void k_merge(AttnParams p, SeqMeta meta) {
   const int len = meta.kv_len[b] + (meta.node_off[b + 1] - meta.node_off[b]);
   const int ns = (len + p.chunk - 1) / p.chunk;
   if (ns <= 1) return;
-  const float* pr = p.partial + row * p.nsplit * (D + 2);
+  constexpr int PS = partial_stride(D);
+  const float* pr = p.partial + row * p.nsplit * PS;
   float m = -INFINITY;
-  for (int t = 0; t < ns; t++) m = fmaxf(m, pr[t * (D + 2) + D]);
+  for (int t = 0; t < ns; t++) m = fmaxf(m, pr[t * PS + D]);
   float l = 0.f, o = 0.f;
   for (int t = 0; t < ns; t++) {
-    const float mt = pr[t * (D + 2) + D];
+    const float mt = pr[t * PS + D];
     const float w = (mt == -INFINITY) ? 0.f : expf(mt - m);
-    l = fmaf(pr[t * (D + 2) + D + 1], w, l);
-    o = fmaf(pr[t * (D + 2) + threadIdx.x], w, o);
+    l = fmaf(pr[t * PS + D + 1], w, l);
+    o = fmaf(pr[t * PS + threadIdx.x], w, o);
   }
   st_elem(reinterpret_cast<T*>(p.out) + row * D + threadIdx.x, o / l);
 }

@@ -9,6 +9,9 @@ namespace cb {
 constexpr int kAncWords = CB_MAX_NODES / 32;  // 256-bit ancestor set per node
 constexpr int kArgmaxChunk = 8192;            // logits elements scanned by one workgroup
 constexpr int kRowTile = 64;                  // query rows per workgroup in the MFMA attention
+// floats per (row, split) partial softmax state: o[D] unnormalised, m, l, padded to 16 bytes
+constexpr int partial_stride(int D) { return D + 4; }
+constexpr int kPartialStrideD128 = partial_stride(128);
 
 // Per-sequence shapes; passed to kernels by value (kernel arguments), so they need no upload and
 // are captured with the launch.
@@ -46,13 +49,16 @@ struct AttnParams {
   void* out;         // [sumN][Hq][D]
   KvAddr kv;
   const uint32_t* anc;  // [sumN][kAncWords]
-  float* partial;       // [sumN*Hq][nsplit][D+2]: o[D] (unnormalised), m, l
+  float* partial;       // [sumN*Hq][nsplit][partial_stride(D)]: o[D] (unnormalised), m, l, pad
   uint32_t* tickets;    // one counter per (sequence, kv head, row tile)
   int32_t Hq, Hkv, D;
   int32_t chunk;        // keys per split
   int32_t nsplit;       // partial slots per row (>= splits any sequence uses)
   int32_t batch;
   float scale;
+  int32_t xcd_remap;    // 1: renumber workgroups so that all splits of a tile run on one XCD
+  int32_t debug_flags;  // bit 0: skip the split merge (timing aid; output then undefined)
+  int32_t* status;      // device status word (bit 4: a merge had to use cross-XCD loads)
 };
 
 struct ArgmaxPartial {

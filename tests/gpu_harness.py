@@ -54,7 +54,7 @@ def run_case(case, rows=None, layout=B.CB_LAYOUT_TOKEN_MAJOR, options=None, max_
         out, acc_len, acc_tok = ver.verify_tree(dc.q, dc.kv, case.kv_len, case.node_offsets, case.parent,
                                                 case.tokens, dc.logits)
         torch.cuda.synchronize()
-        assert ver.device_status() == 0
+        assert ver.device_status() & 3 == 0      # bits 0-1: tree problems; bit 4 only reports a cross-XCD merge
         # ---- argmax / acceptance: bit-exact
         a_ref, res = O.verify(case)
         a_gpu = ver.get_argmax(case.total_nodes)
