@@ -5,11 +5,12 @@ A step is one pass of the whole hot path over one batch of synthetic input: ance
 tree-masked attention (with its split merge), vocabulary argmax, greedy acceptance and KV
 compaction, enqueued through the C ABI (cb_verify_tree_device + cb_compact_kv).  The workload is
 the 7B-shaped configuration (batch 1, 32 heads, head_dim 128, bf16, prefix 2048, 64-node tree from
-the LRU drafter, logits [64, 32000]); inputs are resident in HBM before the timed region.  The
-step rotates over enough independent copies of (q, cache, logits) that every pass reads its K/V
-from HBM rather than from the 256 MB last-level cache.
+the LRU drafter, logits [64, 32000]); inputs are resident in HBM before the timed region.  Steps
+rotate over enough independent copies of (q, cache, logits) that every pass reads its K/V from HBM
+rather than from the 256 MB last-level cache (--warm keeps one copy instead).
 
-Prints one JSON line (see README for the fields).
+The steps are captured into a HIP graph (one graph holds one step per input copy) and the graph is
+replayed; --no-graph launches them one by one from Python instead.  Prints one JSON line.
 """
 import argparse
 import json
@@ -27,16 +28,18 @@ HBM_PEAK_GBPS = 8000.0
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default: the 7B-shaped one)")
-    ap.add_argument("--copies", type=int, default=0, help="independent input copies to rotate over (0 = enough for 768 MB)")
-    ap.add_argument("--warm", action="store_true", help="single buffer (cache-resident) instead of rotating copies")
+    ap.add_argument("--copies", type=int, default=0, help="independent input copies to rotate over (0 = about 768 MB worth)")
+    ap.add_argument("--warm", action="store_true", help="one input copy (cache-resident) instead of rotating copies")
     ap.add_argument("--layout", type=int, default=0, help="0 token-major cache, 1 head-major")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--impl", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--attn-iters", type=int, default=0, help="launches in the attention-only timing loop (0 = steps)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: 50 attention launches, then one 256 MiB device copy as the calibration kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -55,7 +58,7 @@ def main():
     attn_bytes = case.attention_bytes()
     per_copy = attn_bytes + case.logits_bytes()
     copies = 1 if args.warm else (args.copies or max(2, -(-768 * 2 ** 20 // per_copy)))
-    copies = min(copies, max(1, int(200e9 // per_copy)))
+    copies = max(1, min(copies, int(160e9 // per_copy)))
     dcs = [B.DeviceCase(case, layout=args.layout) for _ in range(copies)]
     ver = B.Verifier(B.config_for_case(case, max_splits=72 if args.config == 4 else 0))
     if args.splits:
@@ -67,49 +70,86 @@ def main():
     outs = [torch.empty_like(dc.q) for dc in dcs]
     d_len = torch.zeros(case.B, dtype=torch.int32, device="cuda")
     d_acc = torch.zeros(case.B, case.max_depth + 1, dtype=torch.int32, device="cuda")
-    stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream()          # a non-default stream: needed for graph capture, used for everything
 
-    def step(i):
-        dc = dcs[i % copies]
-        ver.verify_tree_device(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits,
-                               outs[i % copies], d_len, d_acc, stream=stream)
-        ver.compact_kv([dc.kv], case.B, want_len=False, stream=stream)
+    def bound_calls(with_compact):
+        return [ver.bind_step(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits, outs[i], d_len, d_acc,
+                              [dc.kv] if with_compact else [], stream=side) for i, dc in enumerate(dcs)]
+
+    def make_runner(with_compact):
+        """Returns (run(n_groups), steps_per_group): one group = one step on every input copy."""
+        calls = bound_calls(with_compact)
+        if args.no_graph:
+            def run(n):
+                for _ in range(n):
+                    for c in calls:
+                        c()
+            return run, len(calls), "launches"
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            for c in calls[:2]:
+                c()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for c in calls:
+                    c()
+
+        def run(n):
+            with torch.cuda.stream(side):
+                for _ in range(n):
+                    graph.replay()
+        return run, len(calls), "hipGraph"
+
+    if args.traffic_probe:
+        ver.set_option("stages", 3)
+        bound_calls(False)[0]()
+        ver.set_option("stages", 2)
+        calls = bound_calls(False)
+        for i in range(50):
+            calls[i % copies]()
+        side.synchronize()
+        a = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "attention_launches": 50, "copy_bytes_each_way": a.numel()}))
+        return
 
     # ---- whole step: W warm-up steps, then exactly K timed steps
-    for i in range(args.warmup):
-        step(i)
+    run, per_group, how = make_runner(True)
+    groups_w = max(1, args.warmup // per_group)
+    groups = max(1, args.steps // per_group)
+    steps, warmup = groups * per_group, groups_w * per_group
+    run(groups_w)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    run(groups)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     accepted = d_len.cpu().tolist()
 
-    # ---- dominant kernel (attention + split merge) alone, HIP events on the launch stream
-    iters = args.attn_iters or args.steps
-
-    def timed_stage(mask, n):
+    # ---- one stage alone (attention incl. its split merge; argmax), HIP events on the launch stream
+    def timed_stage(mask):
+        ver.set_option("stages", 3)
+        bound_calls(False)[0]()            # ancestor sets in place for the stage runs
+        side.synchronize()
         ver.set_option("stages", mask)
-        for i in range(min(50, n)):
-            dc = dcs[i % copies]
-            ver.verify_tree_device(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits,
-                                   outs[i % copies], d_len, d_acc, stream=stream)
+        srun, spg, _ = make_runner(False)
+        ver.set_option("stages", 15)
+        srun(max(1, 100 // spg))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        e0.record(stream)
-        for i in range(n):
-            dc = dcs[i % copies]
-            ver.verify_tree_device(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits,
-                                   outs[i % copies], d_len, d_acc, stream=stream)
-        e1.record(stream)
+        n = max(1, args.steps // spg)
+        e0.record(side)
+        srun(n)
+        e1.record(side)
         e1.synchronize()
-        ver.set_option("stages", 15)
-        return e0.elapsed_time(e1) * 1e3 / n      # microseconds per launch group
+        return e0.elapsed_time(e1) * 1e3 / (n * spg)      # microseconds per launch
 
-    attn_us = timed_stage(2, iters)
-    argmax_us = timed_stage(4, iters)
+    attn_us = timed_stage(2)
+    argmax_us = timed_stage(4)
     attn_gbps = attn_bytes / attn_us / 1e3
 
     out = {
@@ -117,8 +157,8 @@ def main():
         "value": round(1e3 / ms_per_step, 1),
         "unit": "verify steps/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True,
         "scaling": "weak",
@@ -129,7 +169,7 @@ def main():
                                f"prefix={case.kv_len.tolist() if case.B <= 4 else 'ragged'} nodes={case.total_nodes} V={case.V}",
                    "cache": "paged16" if case.block_size else "contiguous",
                    "layout": "token-major" if args.layout == 0 else "head-major",
-                   "input_copies": copies, "cold_cache": not args.warm,
+                   "input_copies": copies, "cold_cache": not args.warm, "launch": how,
                    "accepted_len": accepted[:4]},
         "attention_us": round(attn_us, 3),
         "attention_gbps": round(attn_gbps, 1),
@@ -137,7 +177,7 @@ def main():
         "argmax_us": round(argmax_us, 3),
         "roofline": {"bound": "hbm", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "kernel": "tree attention (k_attn_mfma + split merge)", "algorithmic_bytes": attn_bytes},
+                     "kernel": "cb::k_attn_mfma (tree attention incl. split merge)", "algorithmic_bytes": attn_bytes},
     }
     traffic_file = os.path.join(ROOT, "profiles", "attention_traffic.json")
     if os.path.exists(traffic_file):
@@ -150,28 +190,28 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import cb_oracle as O
         threads = min(O.num_threads(), os.cpu_count() or 1)
-        rows = O.all_rows(case)
-        budget_rows = len(rows)
-        sample = "whole workload"
-        est = case.attention_flops() / 2 / 2.5e9 / max(threads, 1)      # rough seconds at ~2.5 G key-dims/s/core
+        all_rows = O.all_rows(case)
+        rows, sample = all_rows, "whole workload"
+        est = case.attention_flops() / 4 / 1.5e9 / max(threads, 1)      # rough seconds, ~1.5 G multiply-adds/s/core
         if est > 20:
-            budget_rows = max(threads, int(len(rows) * 20 / est))
-            rows = rows[np.linspace(0, len(rows) - 1, budget_rows).astype(int)]
-            sample = f"{budget_rows} of {len(O.all_rows(case))} attention rows (evenly spaced), scaled; argmax/accept/compact whole"
+            keep = max(threads, int(len(all_rows) * 20 / est))
+            rows = all_rows[np.linspace(0, len(all_rows) - 1, keep).astype(int)]
+            sample = f"attention: {keep} of {len(all_rows)} rows evenly spaced, time scaled up; argmax, acceptance, compaction: whole"
         t0 = time.perf_counter()
         O.attention_rows(case, rows, threads=threads)
-        t_attn = (time.perf_counter() - t0) * (len(O.all_rows(case)) / len(rows))
+        t_attn = (time.perf_counter() - t0) * (len(all_rows) / len(rows))
         t0 = time.perf_counter()
         a, res = O.verify(case)
+        t_verify = time.perf_counter() - t0
         k2, v2 = case.k.copy(), case.v.copy()
-        t_copy0 = time.perf_counter()
+        t0 = time.perf_counter()
         for b, (L, path, toks) in enumerate(res):
             O.compact(case, k2, v2, b, path)
-        t_rest = (time.perf_counter() - t0) - (t_copy0 - t0) + 0.0
-        t_rest += 0.0
-        total = t_attn + t_rest
+        t_compact = time.perf_counter() - t0
+        total = t_attn + t_verify + t_compact
         out["cpu_baseline"] = {"value": round(1.0 / total, 3), "unit": "verify steps/s", "cores": threads, "kind": "oracle",
-                               "sample": sample, "attention_s": round(t_attn, 4), "argmax_accept_compact_s": round(t_rest, 4)}
+                               "sample": sample, "attention_s": round(t_attn, 4), "argmax_accept_s": round(t_verify, 4),
+                               "compact_s": round(t_compact, 5)}
     print(json.dumps(out))
 
 

@@ -181,6 +181,12 @@ int cb_set_option(cb_ctx *ctx, const char *name, int64_t value);
  * Synchronises.  Not available under stream capture. */
 int cb_last_attention_ms(cb_ctx *ctx, float *ms);
 
+/* Timing aid: with option "debug_flags" bit 5 (32) set, the MFMA attention kernel stamps eight
+ * 100 MHz clock readings per workgroup (entry, arguments read, loads issued, first stage ready,
+ * key sweep done, partials written, ticket taken, merge done).  Copies those of the first
+ * `workgroups` (<= 1024) workgroups of the last launch to host memory, 8 values each. */
+int cb_debug_timestamps(cb_ctx *ctx, uint64_t *out, int32_t workgroups);
+
 const char *cb_last_error(const cb_ctx *ctx); /* "" when the last call succeeded; ctx may be NULL
                                                  for the error of a failed cb_init */
 void cb_destroy(cb_ctx *ctx);

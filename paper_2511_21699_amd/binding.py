@@ -22,7 +22,7 @@ ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_E
 
 EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_verify_tree", "cb_verify_tree_device",
            "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
-           "cb_last_attention_ms", "cb_last_error", "cb_destroy"]
+           "cb_last_attention_ms", "cb_debug_timestamps", "cb_last_error", "cb_destroy"]
 
 
 class CbConfig(C.Structure):
@@ -67,6 +67,7 @@ def load():
     L.cb_device_status.argtypes = [vp, i32p]
     L.cb_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
     L.cb_last_attention_ms.argtypes = [vp, C.POINTER(C.c_float)]
+    L.cb_debug_timestamps.argtypes = [vp, C.POINTER(C.c_uint64), C.c_int32]
     L.cb_last_error.argtypes = [vp]
     L.cb_last_error.restype = C.c_char_p
     L.cb_destroy.argtypes = [vp]
@@ -184,6 +185,27 @@ class Verifier:
                                           d_acc_tok.data_ptr())
         self._raise(rc)
 
+    def bind_step(self, q, kv: CbKvLayer, kv_len, node_offsets, d_parent, d_tokens, logits, attn_out, d_acc_len,
+                  d_acc_tok, layers: Sequence[CbKvLayer], stream=None):
+        """Pre-marshalled cb_verify_tree_device + cb_compact_kv pair: returns a zero-argument callable that
+        only makes the two C calls (for launch loops where per-call marshalling would dominate)."""
+        kv_len, node_offsets = _i32(kv_len), _i32(node_offsets)
+        arr = (CbKvLayer * len(layers))(*layers) if layers else None
+        st = self._stream(stream)
+        a = (self.ctx, st, kv_len.shape[0], q.data_ptr(), C.byref(kv), _ip(kv_len), _ip(node_offsets),
+             d_parent.data_ptr(), d_tokens.data_ptr(), logits.data_ptr(), attn_out.data_ptr(), d_acc_len.data_ptr(),
+             d_acc_tok.data_ptr())
+        keep = (kv_len, node_offsets, arr, kv, q, logits, attn_out)
+        verify, compact, nl = self.L.cb_verify_tree_device, self.L.cb_compact_kv, len(layers)
+
+        def call(_keep=keep):
+            rc = verify(*a)
+            if rc == 0 and nl:
+                rc = compact(self.ctx, st, nl, arr, None)
+            if rc:
+                self._raise(rc)
+        return call
+
     def compact_kv(self, layers: Sequence[CbKvLayer], batch: int, want_len: bool = True, stream=None):
         arr = (CbKvLayer * len(layers))(*layers)
         new_len = np.zeros(batch, dtype=np.int32)
@@ -208,6 +230,11 @@ class Verifier:
 
     def set_option(self, name: str, value: int):
         self._raise(self.L.cb_set_option(self.ctx, name.encode(), int(value)))
+
+    def debug_timestamps(self, workgroups: int) -> np.ndarray:
+        out = np.zeros((workgroups, 8), dtype=np.uint64)
+        self._raise(self.L.cb_debug_timestamps(self.ctx, out.ctypes.data_as(C.POINTER(C.c_uint64)), workgroups))
+        return out
 
     def last_attention_ms(self) -> float:
         ms = C.c_float(0)

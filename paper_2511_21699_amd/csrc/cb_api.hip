@@ -20,7 +20,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
   size_t anc, parent, tokens, amax_partial, amax_out, path, len_ctx, res_len, res_tok, new_len, status,
-      tickets, partial, total;
+      tickets, dbg, partial, total;
   int amax_chunks;
   int max_total_nodes;
   int max_splits;
@@ -58,7 +58,7 @@ WsLayout ws_layout(const cb_config& c) {
   L.max_splits = effective_max_splits(c);
   L.amax_chunks = (int)(((int64_t)c.vocab_size + kArgmaxChunk - 1) / kArgmaxChunk);
   const int g = c.num_q_heads / c.num_kv_heads;
-  L.ticket_count = 2 * c.max_batch * c.num_kv_heads * ((c.max_nodes * g + kRowTile - 1) / kRowTile);  // (count, XCD mask) pairs
+  L.ticket_count = 2 * c.max_batch * c.num_kv_heads * ((c.max_nodes * g + kRowTile - 1) / kRowTile);  // one 64-bit ticket word per tile
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   L.anc = take(mt * kAncWords * 4);
@@ -73,6 +73,7 @@ WsLayout ws_layout(const cb_config& c) {
   L.new_len = take(c.max_batch * 4);
   L.status = take(4);
   L.tickets = take((size_t)L.ticket_count * 4);
+  L.dbg = take(1024 * 8 * 8);
   L.partial = take(mt * c.num_q_heads * (size_t)L.max_splits * partial_stride(c.head_dim) * 4);
   L.total = o;
   return L;
@@ -231,6 +232,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.batch = batch;
   ap.scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
   ap.status = ctx->dev<int32_t>(ctx->lay.status);
+  ap.dbg_ts = ctx->dev<unsigned long long>(ctx->lay.dbg);
   ap.debug_flags = (int32_t)ctx->opt_debug;
 
   const int64_t stages = ctx->opt_stages;  // measurement aid: bit 0 prepare, 1 attention, 2 argmax, 3 acceptance
@@ -511,6 +513,14 @@ int cb_last_attention_ms(cb_ctx* ctx, float* ms) {
   if (!ctx->ev_valid) return set_err(ctx, CB_ESTATE, "option time_attention was not set for the last verify");
   CB_HIP(ctx, hipEventSynchronize(ctx->ev1));
   CB_HIP(ctx, hipEventElapsedTime(ms, ctx->ev0, ctx->ev1));
+  return CB_OK;
+}
+
+int cb_debug_timestamps(cb_ctx* ctx, uint64_t* out, int32_t workgroups) {
+  if (!ctx || !out || workgroups < 1 || workgroups > 1024) return set_err(ctx, CB_EINVAL, "bad argument");
+  hipStream_t st = ctx->have_verify ? ctx->last_stream : nullptr;
+  CB_HIP(ctx, hipStreamSynchronize(st));
+  CB_HIP(ctx, hipMemcpy(out, ctx->ws + ctx->lay.dbg, (size_t)workgroups * 64, hipMemcpyDeviceToHost));
   return CB_OK;
 }
 

@@ -30,18 +30,18 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uintx4;
 typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned uintx2;
+#define CB_GLOBAL __attribute__((address_space(1)))
 constexpr int kAgentCoherent = 16;  // buffer cache policy: sc1 = coherent at agent (device) scope
 
-constexpr int kStageKeys = 32;                 // keys per LDS stage
+constexpr int kStageKeys = 32;                 // keys per LDS stage and wave group
 constexpr int kStageVecs = kStageKeys * 16;    // 16-byte pieces per K (or V) stage: 32 rows x 256 B
 constexpr int NS = 4;                          // ring depth: NS-1 stages in flight
 constexpr int kMaxBtLds = 1024;                // block-table entries staged in LDS per split
-constexpr int kPartialStride = kPartialStrideD128;  // floats per (row, split) partial: o[128], m, l, pad
+// Partial softmax state of one (row, split) in this kernel's own format: o[128] as bf16 (unnormalised,
+// relative to the reference weight), then m and l as fp32, padded to 16 bytes.  Halving the bytes
+// matters because one workgroup pulls all partials of its tile through a single compute unit.
+constexpr int kPartialBytes = 128 * 2 + 16;
 
-// One __shared__ object per ring slot: the compiler tracks LDS-DMA completion per object.
-#define CB_DECL_RING()                                        \
-  __shared__ uint4 K0[kStageVecs], K1[kStageVecs], K2[kStageVecs], K3[kStageVecs]; \
-  __shared__ uint4 V0[kStageVecs], V1[kStageVecs], V2[kStageVecs], V3[kStageVecs];
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -90,8 +90,8 @@ __device__ __forceinline__ void ring_barrier() {
 // which piece of the row lands there is chosen by the XOR swizzle so that the MFMA operand reads
 // below are free of bank conflicts.  Keys past the end are clamped to the last valid one (they
 // are masked in the softmax), so every address stays inside the cache.
-__device__ __forceinline__ void issue_stage(uint4* kdst, uint4* vdst, const KeyAddr& ka, const char* kbase,
-                                            const char* vbase, int key0, int last_key, int w, int l) {
+__device__ __forceinline__ void issue_stage(uint4* kdst, uint4* vdst, const KeyAddr& ka, const CB_GLOBAL char* kbase,
+                                            const CB_GLOBAL char* vbase, int key0, int last_key, int w, int l) {
 #pragma unroll
   for (int i = 0; i < 2; i++) {
     const int r = 8 * w + 4 * i + (l >> 4);
@@ -101,9 +101,9 @@ __device__ __forceinline__ void issue_stage(uint4* kdst, uint4* vdst, const KeyA
     const int64_t off = ka.byte_off(key);
     const int pk = c ^ (r & 15);
     const int pv = c ^ ((r & 7) << 1);
-    __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(kbase + off + pk * 16),
+    __builtin_amdgcn_global_load_lds((const CB_GLOBAL uint32_t*)(kbase + off + pk * 16),
                                      (__attribute__((address_space(3))) void*)(kdst + (8 * w + 4 * i) * 16), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(vbase + off + pv * 16),
+    __builtin_amdgcn_global_load_lds((const CB_GLOBAL uint32_t*)(vbase + off + pv * 16),
                                      (__attribute__((address_space(3))) void*)(vdst + (8 * w + 4 * i) * 16), 16, 0, 0);
   }
 }
@@ -231,95 +231,149 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
   }
 }
 
-// Split merge for the rows of one tile: thread -> (row, 32-dim quarter);
-// m = max m_t, w_t = e^(m_t - m), o = sum w_t o_t / sum w_t l_t.  POL is the buffer cache policy.
-template <int R, int POL>
+// Forces every field of the argument block into scalar registers here and now: the empty asm
+// statements take each value as an in/out operand, so the loads cannot be sunk past this point.
+#define CB_PIN(x) asm volatile("" : "+s"(x))
+__device__ __forceinline__ void pin_args(AttnParams& p) {
+  CB_PIN(p.q); CB_PIN(p.out); CB_PIN(p.kv.k); CB_PIN(p.kv.v); CB_PIN(p.kv.block_table);
+  CB_PIN(p.kv.seq_stride); CB_PIN(p.kv.token_stride); CB_PIN(p.kv.head_stride); CB_PIN(p.kv.num_blocks);
+  CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.anc); CB_PIN(p.partial); CB_PIN(p.tickets);
+  CB_PIN(p.Hq); CB_PIN(p.Hkv); CB_PIN(p.chunk); CB_PIN(p.nsplit); CB_PIN(p.batch); CB_PIN(p.scale);
+  CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags);
+  CB_PIN(p.status); CB_PIN(p.dbg_ts);
+}
+#undef CB_PIN
+
+// Split merge for the rows of one tile by all NT threads of the workgroup: thread -> (row, slice
+// of DPT dims).  Partials are combined online, BS splits per batch with all of a batch's loads in
+// flight together: m = max m_t, w_t = e^(m_t - m), o = sum w_t o_t / sum w_t l_t.
+// POL is the buffer cache policy of the loads.
+template <int R, int G, int POL>
 __device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_rsrc_t prsrc, int64_t seq_row0,
                                            int row0, int M, int g, int off, int hk, int nsplit_b, int tid) {
   constexpr int D = 128;
-  const int quarter = tid & 3;
-  for (int rl = tid >> 2; rl < 64 * R; rl += 64) {
+  constexpr int SL = 4 * G;        // slices per row
+  constexpr int DPT = D / SL;      // dims per thread
+  constexpr int VPT = DPT / 8;     // 16-byte loads (8 bf16) per split and thread
+  constexpr int BS = 16 / VPT;     // splits per batch
+  const int slice = tid % SL;
+  for (int rl = tid / SL; rl < 64 * R; rl += 64) {
     const int row = row0 + rl;
     if (row >= M) break;
     const int node = row / g, hg = row - node * g;
     const int64_t gr = (int64_t)(off + node) * p.Hq + hk * g + hg;
-    const uint32_t rbyte = (uint32_t)((gr - seq_row0) * p.nsplit * (kPartialStride * 4));
-    float m = -INFINITY;
-    for (int t = 0; t < nsplit_b; t++)
-      m = fmaxf(m, __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(prsrc, rbyte + (t * kPartialStride + D) * 4, 0, POL)));
-    float acc[32];
+    const uint32_t rbyte = (uint32_t)((gr - seq_row0) * p.nsplit * kPartialBytes);
+    float acc[DPT];
 #pragma unroll
-    for (int i = 0; i < 32; i++) acc[i] = 0.f;
-    float lsum = 0.f;
-    for (int t0 = 0; t0 < nsplit_b; t0 += 2) {  // two splits' loads in flight together
-      uintx4 v[2][8];
-      uintx2 ml[2];
+    for (int i = 0; i < DPT; i++) acc[i] = 0.f;
+    float lsum = 0.f, m_run = -INFINITY;
+    for (int t0 = 0; t0 < nsplit_b; t0 += BS) {
+      uintx4 v[BS][VPT];
+      uintx2 ml[BS];
 #pragma unroll
-      for (int u = 0; u < 2; u++) {
-        const int t = (t0 + u < nsplit_b) ? t0 + u : t0;
-        const uint32_t tb = rbyte + t * (kPartialStride * 4);
-        ml[u] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + D * 4, 0, POL);
+      for (int u = 0; u < BS; u++) {
+        const int t = (t0 + u < nsplit_b) ? t0 + u : nsplit_b - 1;
+        const uint32_t tb = rbyte + t * kPartialBytes;
+        ml[u] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + D * 2, 0, POL);
 #pragma unroll
-        for (int i = 0; i < 8; i++)
-          v[u][i] = __builtin_amdgcn_raw_buffer_load_b128(prsrc, tb + (quarter * 32 + 4 * i) * 4, 0, POL);
+        for (int i = 0; i < VPT; i++)
+          v[u][i] = __builtin_amdgcn_raw_buffer_load_b128(prsrc, tb + (slice * DPT + 8 * i) * 2, 0, POL);
       }
+      float mb = -INFINITY;
 #pragma unroll
-      for (int u = 0; u < 2; u++) {
+      for (int u = 0; u < BS; u++)
+        if (t0 + u < nsplit_b) mb = fmaxf(mb, __uint_as_float(ml[u][0]));
+      const float m_new = fmaxf(m_run, mb);
+      const float resc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+#pragma unroll
+      for (int i = 0; i < DPT; i++) acc[i] *= resc;
+      lsum *= resc;
+      m_run = m_new;
+#pragma unroll
+      for (int u = 0; u < BS; u++) {
         const float mt = __uint_as_float(ml[u][0]);
-        float wgt = (mt == -INFINITY) ? 0.f : __expf(mt - m);
-        if (t0 + u >= nsplit_b) wgt = 0.f;
+        const float wgt = (t0 + u < nsplit_b && mt != -INFINITY) ? __expf(mt - m_new) : 0.f;
         lsum = fmaf(__uint_as_float(ml[u][1]), wgt, lsum);
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-          acc[4 * i + 0] = fmaf(__uint_as_float(v[u][i][0]), wgt, acc[4 * i + 0]);
-          acc[4 * i + 1] = fmaf(__uint_as_float(v[u][i][1]), wgt, acc[4 * i + 1]);
-          acc[4 * i + 2] = fmaf(__uint_as_float(v[u][i][2]), wgt, acc[4 * i + 2]);
-          acc[4 * i + 3] = fmaf(__uint_as_float(v[u][i][3]), wgt, acc[4 * i + 3]);
-        }
+        for (int i = 0; i < VPT; i++)
+#pragma unroll
+          for (int k = 0; k < 4; k++) {
+            acc[8 * i + 2 * k] = fmaf(__uint_as_float(v[u][i][k] << 16), wgt, acc[8 * i + 2 * k]);
+            acc[8 * i + 2 * k + 1] = fmaf(__uint_as_float(v[u][i][k] & 0xffff0000u), wgt, acc[8 * i + 2 * k + 1]);
+          }
       }
     }
     const float inv = 1.0f / lsum;
-    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(p.out) + gr * D + quarter * 32);
+    CB_GLOBAL uintx4* dst = (CB_GLOBAL uintx4*)((CB_GLOBAL uint16_t*)p.out + gr * D + slice * DPT);
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      uint4 pk;
-      pk.x = (uint32_t)f2bf(acc[8 * i + 0] * inv) | ((uint32_t)f2bf(acc[8 * i + 1] * inv) << 16);
-      pk.y = (uint32_t)f2bf(acc[8 * i + 2] * inv) | ((uint32_t)f2bf(acc[8 * i + 3] * inv) << 16);
-      pk.z = (uint32_t)f2bf(acc[8 * i + 4] * inv) | ((uint32_t)f2bf(acc[8 * i + 5] * inv) << 16);
-      pk.w = (uint32_t)f2bf(acc[8 * i + 6] * inv) | ((uint32_t)f2bf(acc[8 * i + 7] * inv) << 16);
+    for (int i = 0; i < DPT / 8; i++) {
+      uintx4 pk;
+      pk[0] = (uint32_t)f2bf(acc[8 * i + 0] * inv) | ((uint32_t)f2bf(acc[8 * i + 1] * inv) << 16);
+      pk[1] = (uint32_t)f2bf(acc[8 * i + 2] * inv) | ((uint32_t)f2bf(acc[8 * i + 3] * inv) << 16);
+      pk[2] = (uint32_t)f2bf(acc[8 * i + 4] * inv) | ((uint32_t)f2bf(acc[8 * i + 5] * inv) << 16);
+      pk[3] = (uint32_t)f2bf(acc[8 * i + 6] * inv) | ((uint32_t)f2bf(acc[8 * i + 7] * inv) << 16);
       dst[i] = pk;
     }
   }
 }
 
-// grid: x = split, y = kv head + Hkv * row tile, z = sequence
-template <int R>
-__global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
-  CB_DECL_RING()
+// grid: x = split, y = kv head + Hkv * row tile, z = sequence; block = 256 * G threads.
+// G wave groups share the 64*R rows of the tile: group gi takes keys [32 gi, 32 gi + 32) of every
+// 32*G-key stage, so with G = 2 each SIMD holds two waves whose MFMA, LDS and vector phases
+// overlap; their softmax states are combined through LDS before the partial is written.
+template <int R, int G>
+__global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta meta) {
+  static_assert(G == 1 || (G == 2 && R == 1), "two wave groups are only built for one row tile per wave");
+  // All kernel arguments are fetched in one burst at entry (see pin_args): left to itself the
+  // compiler loads each near its first use, behind early exits, and the chain of dependent scalar
+  // loads then costs several microseconds before the first K/V request goes out.
+  const unsigned long long ts0 = wall_clock64();
+  const SeqMetaLanes ml = seq_meta_prefetch(meta);
+  AttnParams p = p_arg;
+  pin_args(p);
+  // (the pinned pointers have lost their address space: say again that they are global memory)
+  const CB_GLOBAL uint16_t* gq = (const CB_GLOBAL uint16_t*)p.q;
+  CB_GLOBAL uint16_t* gout = (CB_GLOBAL uint16_t*)p.out;
+  const CB_GLOBAL char* kbase = (const CB_GLOBAL char*)p.kv.k;
+  const CB_GLOBAL char* vbase = (const CB_GLOBAL char*)p.kv.v;
+  const CB_GLOBAL int32_t* gbt = (const CB_GLOBAL int32_t*)p.kv.block_table;
+  const CB_GLOBAL uint32_t* ganc = (const CB_GLOBAL uint32_t*)p.anc;
+  constexpr int NT = 256 * G;
+  constexpr int SK = kStageKeys * G;  // keys per stage
+  constexpr int SV = kStageVecs * G;  // 16-byte pieces of K (or V) per stage
+  __shared__ uint4 K0[SV], K1[SV], K2[SV], K3[SV];  // one object per ring slot: the compiler tracks
+  __shared__ uint4 V0[SV], V1[SV], V2[SV], V3[SV];  // LDS-DMA completion per object
   __shared__ int bt_lds[kMaxBtLds];
   __shared__ uint32_t anc_lds[64 * R * kAncWords];
+  __shared__ int last_flag;
   constexpr int D = 128;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+  const int gi = w >> 2, wi = w & 3;
   const int c = l & 15, kg = l >> 4;
   // Workgroups are handed to the 8 XCDs round-robin in dispatch order.  With xcd_remap the
   // dispatch index d is renumbered to j = (d % 8) * (T / 8) + d / 8, so that consecutive j --
-  // in particular all splits of one (sequence, kv head, row tile), and the row tiles that share
-  // a K/V chunk -- sit on the same XCD and meet in its L2.
+  // in particular all splits of one (sequence, kv head, row tile) -- sit on the same XCD and
+  // meet in its L2.
   int split, by, b;
   {
-    const int T = gridDim.x * gridDim.y * gridDim.z;
-    const int d = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int T = p.grid_x * p.grid_y * p.grid_z;
+    const int d = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
     const int j = p.xcd_remap ? (d & 7) * (T >> 3) + (d >> 3) : d;
-    split = j % (int)gridDim.x;
-    const int rest = j / (int)gridDim.x;
-    by = rest % (int)gridDim.y;
-    b = rest / (int)gridDim.y;
+    split = j % p.grid_x;
+    const int rest = j / p.grid_x;
+    by = rest % p.grid_y;
+    b = rest / p.grid_y;
   }
   const int hk = by % p.Hkv, rt = by / p.Hkv;
   const int g = p.Hq / p.Hkv;
-  const int off = meta.node_off[b];
-  const int N = meta.node_off[b + 1] - off;
-  const int S = meta.kv_len[b];
+  const SeqShape shp = seq_shape(ml, b);
+  const int wg_linear = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
+  CB_GLOBAL unsigned long long* ts = (CB_GLOBAL unsigned long long*)p.dbg_ts + (int64_t)wg_linear * 8;
+  const bool do_ts = (p.debug_flags & 32) && threadIdx.x == 0 && wg_linear < 1024;
+#define CB_TS(i) do { if (do_ts) ts[i] = wall_clock64(); } while (0)
+  if (do_ts) ts[0] = ts0;
+  CB_TS(1);
+  const int off = shp.off, N = shp.N, S = shp.S;
   const int M = N * g;
   const int row0 = rt * 64 * R;
   if (row0 >= M) return;
@@ -327,7 +381,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
   const int k0 = split * p.chunk;
   if (k0 >= len) return;
   const int k1 = (k0 + p.chunk < len) ? k0 + p.chunk : len;
-  const int nst = (k1 - k0 + kStageKeys - 1) / kStageKeys;
+  const int nst = (k1 - k0 + SK - 1) / SK;
   const int nsplit_b = (len + p.chunk - 1) / p.chunk;
 
   KeyAddr ka;
@@ -340,25 +394,19 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
   if (p.kv.block_size > 0) {  // the launcher guarantees a power-of-two block size and a slice that fits
     ka.bs_shift = 31 - __clz(p.kv.block_size);
     const int first = k0 >> ka.bs_shift, last = (k1 - 1) >> ka.bs_shift;
-    for (int i = tid; i <= last - first && i < kMaxBtLds; i += 256)
-      bt_lds[i] = p.kv.block_table[(int64_t)b * p.kv.max_blocks + first + i];
+    for (int i = tid; i <= last - first && i < kMaxBtLds; i += NT)
+      bt_lds[i] = gbt[(int64_t)b * p.kv.max_blocks + first + i];
     ka.bt_first = first;
+    __syncthreads();  // the K/V addresses below depend on it
   }
-  const bool tree_split = k1 > S;  // this split reaches the tree nodes: masks needed
-  if (tree_split) {
-    for (int i = tid; i < 64 * R * kAncWords; i += 256) {
-      int row = row0 + i / kAncWords;
-      row = row < M ? row : M - 1;
-      anc_lds[i] = p.anc[(int64_t)(off + row / g) * kAncWords + (i % kAncWords)];
-    }
-  }
-  // this wave's rows: query c of row tile rr is row  row0 + (w*R + rr)*16 + c
+  // Everything this workgroup needs from memory is requested up front, oldest first: the query rows
+  // and ancestor words (to registers), then NS-1 stages of K/V (to LDS).
   WaveState<R> st;
   int row_local[R];   // row index inside the workgroup's tile (for anc_lds)
   int64_t grow[R];    // global output row (node * Hq + head), or -1 past the end
 #pragma unroll
   for (int rr = 0; rr < R; rr++) {
-    const int rl = (w * R + rr) * 16 + c;
+    const int rl = (wi * R + rr) * 16 + c;
     int row = row0 + rl;
     const bool valid = row < M;
     row = valid ? row : M - 1;
@@ -366,7 +414,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
     row_local[rr] = valid ? rl : (M - 1 - row0);
     const int64_t gr = (int64_t)(off + node) * p.Hq + hk * g + hg;
     grow[rr] = valid ? gr : -1;
-    const uint4* qp = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.q) + gr * D);
+    const CB_GLOBAL uintx4* qp = (const CB_GLOBAL uintx4*)(gq + gr * D);
 #pragma unroll
     for (int ds = 0; ds < 4; ds++) st.q[rr][ds] = __builtin_bit_cast(bf16x8, qp[kg + 4 * ds]);
 #pragma unroll
@@ -374,19 +422,36 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
     st.lacc[rr] = floatx4{0.f, 0.f, 0.f, 0.f};
     st.mref[rr] = -INFINITY;
   }
-  __syncthreads();  // bt_lds / anc_lds visible
+  const bool tree_split = k1 > S;  // this split reaches the tree nodes: masks needed
+  constexpr int kAncPerThread = (64 * R * kAncWords + NT - 1) / NT;
+  uint32_t ancv[kAncPerThread];
+  if (tree_split) {
+#pragma unroll
+    for (int i = 0; i < kAncPerThread; i++) {
+      const int idx = tid + i * NT;
+      int row = row0 + idx / kAncWords;
+      row = row < M ? row : M - 1;
+      ancv[i] = (idx < 64 * R * kAncWords) ? ganc[(int64_t)(off + row / g) * kAncWords + (idx % kAncWords)] : 0u;
+    }
+  }
 
-  const char* kbase = reinterpret_cast<const char*>(p.kv.k);
-  const char* vbase = reinterpret_cast<const char*>(p.kv.v);
   const float c2 = p.scale * 1.4426950408889634f;  // softmax scale in the log2 domain
   const int last_key = len - 1;
 
-#define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * kStageKeys, last_key, w, l)
-  // prologue: NS-1 stages in flight
+#define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * SK, last_key, w, l)
   if (!(p.debug_flags & 4)) {  // (timing aid: bit 2 leaves the loads out, bit 1 the arithmetic)
     if (0 < nst) CB_ISSUE(0, 0);
     if (1 < nst) CB_ISSUE(1, 1);
     if (2 < nst) CB_ISSUE(2, 2);
+  }
+  CB_TS(2);
+  if (tree_split) {
+#pragma unroll
+    for (int i = 0; i < kAncPerThread; i++) {
+      const int idx = tid + i * NT;
+      if (idx < 64 * R * kAncWords) anc_lds[idx] = ancv[i];
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // written before the first ring barrier below
   }
 
 #define CB_STAGE(J, JPREV)                                                                         \
@@ -396,11 +461,13 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
       const int after = nst - 1 - s; /* stages issued after this one, at most NS-2 */             \
       if (after >= 2) wait_vmcnt<8>(); else if (after == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); \
       ring_barrier();                                                                              \
+      if (s == 0) CB_TS(3);                                                                        \
       if (s + NS - 1 < nst && !(p.debug_flags & 4)) CB_ISSUE(JPREV, s + NS - 1);                   \
-      const int key0 = k0 + s * kStageKeys;                                                        \
+      const int key0 = k0 + s * SK + gi * kStageKeys;                                              \
       const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                      \
-      if (!(p.debug_flags & 2))                                                                    \
-        compute_stage<R>(K##J, V##J, st, c2, key0, S, k1, need_mask, anc_lds, row_local, l);       \
+      if (key0 < k1 && !(p.debug_flags & 2))                                                       \
+        compute_stage<R>(K##J + gi * kStageVecs, V##J + gi * kStageVecs, st, c2, key0, S, k1,      \
+                         need_mask, anc_lds, row_local, l);                                        \
     }                                                                                              \
   }
   for (int s0 = 0; s0 < nst; s0 += NS) {
@@ -412,41 +479,75 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
 #undef CB_STAGE
 #undef CB_ISSUE
 
+  CB_TS(4);
   if (p.debug_flags & 8) return;  // (timing aid: stop after the key sweep)
+
+  if constexpr (G == 2) {
+    // combine the two wave groups' softmax states: group 1 parks (o, mref, l) in the ring, group 0 adds it
+    __syncthreads();  // every wave is done with the ring
+    const int lane = wi * 64 + l;
+    if (gi == 1) {
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        K0[dt * 256 + lane] = __builtin_bit_cast(uint4, st.o[0][dt]);
+        K1[dt * 256 + lane] = __builtin_bit_cast(uint4, st.o[0][dt + 4]);
+      }
+      reinterpret_cast<float2*>(V0)[lane] = float2{st.mref[0], st.lacc[0][0]};
+    }
+    __syncthreads();
+    if (gi == 0) {
+      const float2 ml = reinterpret_cast<const float2*>(V0)[lane];
+      const float m = fmaxf(st.mref[0], ml.x);
+      const float mu = (m == -INFINITY) ? 0.f : m;
+      const float w0 = __builtin_amdgcn_exp2f((st.mref[0] - mu) * c2), w1 = __builtin_amdgcn_exp2f((ml.x - mu) * c2);
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        const floatx4 a = __builtin_bit_cast(floatx4, K0[dt * 256 + lane]);
+        const floatx4 bq = __builtin_bit_cast(floatx4, K1[dt * 256 + lane]);
+        st.o[0][dt] = st.o[0][dt] * w0 + a * w1;
+        st.o[0][dt + 4] = st.o[0][dt + 4] * w0 + bq * w1;
+      }
+      st.lacc[0][0] = st.lacc[0][0] * w0 + ml.y * w1;
+      st.mref[0] = m;
+    }
+  }
+
   // Buffer descriptor over this sequence's partials (byte offsets fit 32 bits, checked by the launcher).
   const int64_t seq_row0 = (int64_t)off * p.Hq;
   const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
-      p.partial + seq_row0 * p.nsplit * kPartialStride, 0, 0x7fffffff, 0x00020000);
-  // finish.  Every lane holds its query's full denominator (all four accumulator entries equal).
+      reinterpret_cast<char*>(p.partial) + seq_row0 * p.nsplit * kPartialBytes, 0, 0x7fffffff, 0x00020000);
+  // finish.  Every lane holds its query's full denominator.
+  if (gi == 0) {
 #pragma unroll
-  for (int rr = 0; rr < R; rr++) {
-    const float lt = st.lacc[rr][0];
-    if (grow[rr] < 0) continue;
-    if (nsplit_b == 1) {
-      const float inv = 1.0f / lt;
-      uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + grow[rr] * D;
+    for (int rr = 0; rr < R; rr++) {
+      const float lt = st.lacc[rr][0];
+      if (grow[rr] < 0) continue;
+      if (nsplit_b == 1) {
+        const float inv = 1.0f / lt;
+        CB_GLOBAL uint16_t* orow = gout + grow[rr] * D;
 #pragma unroll
-      for (int dt = 0; dt < 8; dt++) {
-        uint2 pk;
-        pk.x = (uint32_t)f2bf(st.o[rr][dt][0] * inv) | ((uint32_t)f2bf(st.o[rr][dt][1] * inv) << 16);
-        pk.y = (uint32_t)f2bf(st.o[rr][dt][2] * inv) | ((uint32_t)f2bf(st.o[rr][dt][3] * inv) << 16);
-        *reinterpret_cast<uint2*>(orow + 16 * dt + 4 * kg) = pk;
-      }
-    } else {
-      // partial state of this split, written through to memory (agent scope) so that the merging
-      // workgroup, possibly on another XCD with its own L2, can read it without cache flushes
-      const uint32_t pbyte = (uint32_t)(((grow[rr] - seq_row0) * p.nsplit + split) * (kPartialStride * 4));
+        for (int dt = 0; dt < 8; dt++) {
+          uintx2 pk;
+          pk[0] = (uint32_t)f2bf(st.o[rr][dt][0] * inv) | ((uint32_t)f2bf(st.o[rr][dt][1] * inv) << 16);
+          pk[1] = (uint32_t)f2bf(st.o[rr][dt][2] * inv) | ((uint32_t)f2bf(st.o[rr][dt][3] * inv) << 16);
+          *(CB_GLOBAL uintx2*)(orow + 16 * dt + 4 * kg) = pk;
+        }
+      } else {
+        // partial state of this split, written through to memory (agent scope) so that the merging
+        // workgroup, possibly on another XCD with its own L2, can read it without cache flushes
+        const uint32_t pbyte = (uint32_t)(((grow[rr] - seq_row0) * p.nsplit + split) * kPartialBytes);
 #pragma unroll
-      for (int dt = 0; dt < 8; dt++) {
-        const uintx4 v = {__float_as_uint(st.o[rr][dt][0]), __float_as_uint(st.o[rr][dt][1]),
-                          __float_as_uint(st.o[rr][dt][2]), __float_as_uint(st.o[rr][dt][3])};
-        __builtin_amdgcn_raw_buffer_store_b128(v, prsrc, pbyte + (16 * dt + 4 * kg) * 4, 0, kAgentCoherent);
-      }
-      if (kg == 0) {
-        // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
-        const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
-        const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
-        __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 4, 0, kAgentCoherent);
+        for (int dt = 0; dt < 8; dt++) {
+          const uintx2 v = {(uint32_t)f2bf(st.o[rr][dt][0]) | ((uint32_t)f2bf(st.o[rr][dt][1]) << 16),
+                            (uint32_t)f2bf(st.o[rr][dt][2]) | ((uint32_t)f2bf(st.o[rr][dt][3]) << 16)};
+          __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, kAgentCoherent);
+        }
+        if (kg == 0) {
+          // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
+          const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
+          const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
+          __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, kAgentCoherent);
+        }
       }
     }
   }
@@ -455,39 +556,44 @@ __global__ __launch_bounds__(256) void k_attn_mfma(AttnParams p, SeqMeta meta) {
   // ---- split merge by the last workgroup of this (sequence, kv head, row tile) to finish.
   // The partials above are write-through stores; once they have completed (vmcnt 0) the workgroup
   // takes a ticket with a device-scope atomic.  The workgroup that draws the last ticket reads all
-  // partials of the tile with agent-coherent loads.  No cache-wide write-back or invalidate is
-  // involved (a __threadfence() per workgroup costs a full L2 sweep on this chip).
-  __shared__ int last_flag;
+  // partials of the tile.  No cache-wide write-back or invalidate is involved (a __threadfence()
+  // per workgroup costs a full L2 sweep on this chip).
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  CB_TS(5);
   if (p.debug_flags & 1) return;
-  const int tiles = gridDim.y / p.Hkv;
-  uint32_t* ticket = p.tickets + 2 * (((int64_t)b * p.Hkv + hk) * tiles + rt);
-  // XCC_ID hardware register (id 20, bits 3:0): which XCD this workgroup runs on
-  const uint32_t my_xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
+  const int tiles = p.grid_y / p.Hkv;
+  CB_GLOBAL unsigned long long* ticket =
+      (CB_GLOBAL unsigned long long*)p.tickets + (((int64_t)b * p.Hkv + hk) * tiles + rt);
   if (tid == 0) {
-    __hip_atomic_fetch_or(ticket + 1, 1u << my_xcc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    const uint32_t old = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    int flag = (old == (uint32_t)(nsplit_b - 1)) ? 1 : 0;
+    // One 64-bit atomic carries the arrival count (bits 0-15) and, to learn whether every split ran
+    // on this XCD, the sum (bits 16-35) and sum of squares (bits 36-59) of the arrivals' XCC_ID
+    // (hardware register 20, bits 3:0): all ids equal mine  <=>  sum = n*id and sumsq = n*id*id.
+    const unsigned long long x = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
+    const unsigned long long mine = 1ull | (x << 16) | ((x * x) << 36);
+    const unsigned long long tot = __hip_atomic_fetch_add(ticket, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+    const unsigned long long n = tot & 0xffffull;
+    int flag = (n == (unsigned long long)nsplit_b) ? 1 : 0;
     if (flag) {
-      const uint32_t mask = __hip_atomic_load(ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (mask != (1u << my_xcc)) {
+      const unsigned long long sum = (tot >> 16) & 0xfffffull, sumsq = tot >> 36;
+      if (sum != n * x || sumsq != n * x * x) {
         flag = 2;  // some split ran on another XCD: its partials are not in this L2
-        atomicOr(p.status, 16);
+        __hip_atomic_fetch_or((CB_GLOBAL int32_t*)p.status, 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
-      __hip_atomic_store(ticket + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
     }
     last_flag = flag;
   }
   __syncthreads();
+  CB_TS(6);
   if (!last_flag) return;
   // Same XCD: the write-through stores left the lines in this L2, plain (cached) loads are coherent
   // with them.  Otherwise read past the L2 with agent-coherent loads.
-  const int pol = (last_flag == 2) ? kAgentCoherent : 0;
-  if (pol == 0) merge_rows<R, 0>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
-  else merge_rows<R, kAgentCoherent>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
+  if (last_flag == 1) merge_rows<R, G, 0>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
+  else merge_rows<R, G, kAgentCoherent>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  CB_TS(7);
+#undef CB_TS
 }
 
 bool attn_mfma_supports(const AttnParams& p) {
@@ -496,8 +602,9 @@ bool attn_mfma_supports(const AttnParams& p) {
     if (p.kv.block_size & (p.kv.block_size - 1)) return false;
     if (p.chunk / p.kv.block_size + 2 > kMaxBtLds) return false;
   }
+  if (p.nsplit > 4096) return false;  // the ticket counts arrivals in 16 bits
   // partial offsets inside one sequence are 32-bit byte offsets of a buffer descriptor
-  if ((int64_t)CB_MAX_NODES * p.Hq * p.nsplit * kPartialStride * 4 >= (1ll << 31)) return false;
+  if ((int64_t)CB_MAX_NODES * p.Hq * p.nsplit * kPartialBytes >= (1ll << 31)) return false;
   return true;
 }
 
@@ -512,9 +619,14 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   const int64_t T = (int64_t)p.nsplit * p.Hkv * tiles * p.batch;
   // renumbering needs whole groups of splits inside each XCD's share of the grid
   q.xcd_remap = (T % 8 == 0 && (T / 8) % p.nsplit == 0) ? 1 : 0;
-  if (R == 1) hipLaunchKernelGGL(k_attn_mfma<1>, grid, dim3(256), 0, st, q, meta);
-  else if (R == 2) hipLaunchKernelGGL(k_attn_mfma<2>, grid, dim3(256), 0, st, q, meta);
-  else hipLaunchKernelGGL(k_attn_mfma<4>, grid, dim3(256), 0, st, q, meta);
+  q.grid_x = grid.x;
+  q.grid_y = grid.y;
+  q.grid_z = grid.z;
+  const bool one_group = (p.debug_flags & 16) != 0;  // (timing aid: 4-wave variant for one row tile)
+  if (R == 1 && !one_group) hipLaunchKernelGGL((k_attn_mfma<1, 2>), grid, dim3(512), 0, st, q, meta);
+  else if (R == 1) hipLaunchKernelGGL((k_attn_mfma<1, 1>), grid, dim3(256), 0, st, q, meta);
+  else if (R == 2) hipLaunchKernelGGL((k_attn_mfma<2, 1>), grid, dim3(256), 0, st, q, meta);
+  else hipLaunchKernelGGL((k_attn_mfma<4, 1>), grid, dim3(256), 0, st, q, meta);
   return hipGetLastError();
 }
 

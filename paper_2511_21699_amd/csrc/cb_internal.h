@@ -20,6 +20,32 @@ struct SeqMeta {
   int32_t node_off[CB_MAX_BATCH + 1];
 };
 
+// Shapes of sequence `b` (uniform in the wave) without a dependent scalar load: every lane fetches
+// "its" entry of the argument arrays with one vector load issued at kernel start, and the wanted
+// entry is picked with readlane once b is known.  A chain of scalar loads, each waiting for the
+// one before, costs about a microsecond per link at the start of every workgroup.
+struct SeqShape {
+  int S, off, N;
+};
+struct SeqMetaLanes {
+  int kv, o0, o1;
+};
+__device__ __forceinline__ SeqMetaLanes seq_meta_prefetch(const SeqMeta& meta) {
+  const int lane = threadIdx.x & 63;
+  SeqMetaLanes r;
+  r.kv = meta.kv_len[lane];
+  r.o0 = meta.node_off[lane];
+  r.o1 = meta.node_off[lane + 1];
+  return r;
+}
+__device__ __forceinline__ SeqShape seq_shape(const SeqMetaLanes& m, int b) {
+  SeqShape s;
+  s.S = __builtin_amdgcn_readlane(m.kv, b);
+  s.off = __builtin_amdgcn_readlane(m.o0, b);
+  s.N = __builtin_amdgcn_readlane(m.o1, b) - s.off;
+  return s;
+}
+
 // How to find cache slot (sequence, slot, kv head) in one layer; strides in elements.
 struct KvAddr {
   const void* k;
@@ -57,8 +83,10 @@ struct AttnParams {
   int32_t batch;
   float scale;
   int32_t xcd_remap;    // 1: renumber workgroups so that all splits of a tile run on one XCD
+  int32_t grid_x, grid_y, grid_z;  // launch grid, repeated here so the kernel reads one argument block
   int32_t debug_flags;  // bit 0: skip the split merge (timing aid; output then undefined)
   int32_t* status;      // device status word (bit 4: a merge had to use cross-XCD loads)
+  unsigned long long* dbg_ts;  // timing aid: 8 timestamps (100 MHz) per workgroup when debug bit 5 is set
 };
 
 struct ArgmaxPartial {
