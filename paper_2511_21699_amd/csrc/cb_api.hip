@@ -179,13 +179,38 @@ Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const i
     const int64_t want = 2048;
     nsplit = (int)std::max<int64_t>(1, std::min<int64_t>((want + rows - 1) / rows, (p.max_len + 255) / 256));
   } else {
-    // one workgroup per (64-row tile, kv head, split): fill the 256 compute units about twice over
+    // one workgroup per (row tile of 64, 128 or 256 rows, kv head, split)
     const int g = c.num_q_heads / c.num_kv_heads;
+    const int mrows = p.max_nodes * g;
+    const int rows_per_wg = attn_mfma_tile_rows(mrows);
     int64_t tiles = 0;
     for (int b = 0; b < batch; b++)
-      tiles += (int64_t)(((node_offsets[b + 1] - node_offsets[b]) * g + kRowTile - 1) / kRowTile) * c.num_kv_heads;
-    const int64_t want = 512;
-    nsplit = (int)std::max<int64_t>(1, std::min<int64_t>((want + tiles - 1) / tiles, (p.max_len + 127) / 128));
+      tiles += (int64_t)(((node_offsets[b + 1] - node_offsets[b]) * g + rows_per_wg - 1) / rows_per_wg) * c.num_kv_heads;
+    // Every variant runs 8 waves and a 128 KiB ring: one workgroup per compute unit, so the grid
+    // should come out just under a whole number of rounds of 256 workgroups.  Take the fewest
+    // splits that fill >= 85% of the machine in whole rounds (fewer splits = fewer partials).
+    // efficiency of ns splits: keys swept / (256 units x whole rounds x keys of a full split)
+    auto efficiency = [&](int ns) {
+      const int chunk = ((p.max_len + ns - 1) / ns + 31) / 32 * 32;
+      int64_t t = 0, keys = 0;
+      for (int b = 0; b < batch; b++) {
+        const int n = node_offsets[b + 1] - node_offsets[b];
+        const int64_t tl = (int64_t)((n * g + rows_per_wg - 1) / rows_per_wg) * c.num_kv_heads;
+        t += tl * ((kv_len[b] + n + chunk - 1) / chunk);
+        keys += tl * (kv_len[b] + n);
+      }
+      const int64_t rounds = (t + 255) / 256;
+      return (double)keys / ((double)rounds * 256.0 * chunk);
+    };
+    const int cap = (int)std::max<int64_t>(1, std::min<int64_t>(max_splits, (p.max_len + 127) / 128));
+    nsplit = cap;
+    double best = -1.0;
+    for (int ns = 1; ns <= cap; ns++) {
+      const double eff = efficiency(ns);
+      if (eff >= 0.85) { nsplit = ns; best = eff; break; }
+      if (eff > best) { best = eff; nsplit = ns; }
+    }
+    (void)tiles;
   }
   nsplit = std::max(1, std::min(nsplit, max_splits));
   int chunk = (p.max_len + nsplit - 1) / nsplit;
@@ -243,7 +268,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   if (timing) CB_HIP(ctx, hipEventRecord(ctx->ev0, st));
   if (!(stages & 2)) {
   } else if (plan.impl == 2 && attn_mfma_supports(ap)) {
-    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes));  // merges its own splits
+    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total));  // merges its own splits
   } else {
     CB_HIP(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
     if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));

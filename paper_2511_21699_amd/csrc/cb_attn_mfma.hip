@@ -135,14 +135,37 @@ constexpr float kRescaleSlack = 8.0f;  // log2 units the running maximum may exc
 //   only raised (and O, l rescaled) when the maximum has grown by more than kRescaleSlack, so
 //   probabilities stay below 2^8 and the accumulators are rarely touched by the vector ALU
 //   O^T += V^T P^T, l += 1^T P^T              (9 MFMAs per row tile)
-template <int R>
+// NV <= R is the number of leading row tiles of the wave that hold real rows; the others are skipped.
+template <int R, int NV>
 __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, const uint4* __restrict__ vs,
                                               WaveState<R>& st, float c2, int key0, int S, int kend,
                                               bool need_mask, const uint32_t* anc_lds, const int* row_node, int l) {
   const int c = l & 15, kg = l >> 4;
-  floatx4 s[R][2];
+  // all K operands of the stage are requested before the first MFMA, and all V operands before the
+  // softmax arithmetic, so that LDS latency hides behind the matrix and vector work
+  uint4 kraw[2][4];
 #pragma unroll
-  for (int rr = 0; rr < R; rr++) {
+  for (int sub = 0; sub < 2; sub++) {
+    const int row = 16 * sub + c;
+#pragma unroll
+    for (int ds = 0; ds < 4; ds++) kraw[sub][ds] = ks[row * 16 + ((kg + 4 * ds) ^ (row & 15))];
+  }
+  const char* vbytes = reinterpret_cast<const char*>(vs);
+  bf16x4 va[8][2];
+#pragma unroll
+  for (int dt = 0; dt < 8; dt++) {
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      const int row = 16 * t + 4 * kg + (c >> 2);
+      const int piece = 2 * dt + ((c & 3) >> 1);
+      const int slot = piece ^ ((row & 7) << 1);
+      const char* addr = vbytes + row * 256 + slot * 16 + (c & 1) * 8;
+      va[dt][t] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(addr));
+    }
+  }
+  floatx4 s[NV][2];
+#pragma unroll
+  for (int rr = 0; rr < NV; rr++) {
     s[rr][0] = floatx4{0.f, 0.f, 0.f, 0.f};
     s[rr][1] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
@@ -150,18 +173,15 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
   for (int ds = 0; ds < 4; ds++) {
 #pragma unroll
     for (int sub = 0; sub < 2; sub++) {
-      const int row = 16 * sub + c;
-      const int piece = kg + 4 * ds;
-      const uint4 raw = ks[row * 16 + (piece ^ (row & 15))];
-      const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+      const bf16x8 a = __builtin_bit_cast(bf16x8, kraw[sub][ds]);
 #pragma unroll
-      for (int rr = 0; rr < R; rr++)
+      for (int rr = 0; rr < NV; rr++)
         s[rr][sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, st.q[rr][ds], s[rr][sub], 0, 0, 0);
     }
   }
-  bf16x8 pb[R];
+  bf16x8 pb[NV];
 #pragma unroll
-  for (int rr = 0; rr < R; rr++) {
+  for (int rr = 0; rr < NV; rr++) {
     float x[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) x[e] = s[rr][e >> 2][e & 3];
@@ -208,25 +228,15 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
     pb[rr] = pk.v;
   }
   // O^T += V^T P^T and l += 1^T P^T
-  const char* vbytes = reinterpret_cast<const char*>(vs);
   const bf16x8 ones = __builtin_bit_cast(bf16x8, uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
 #pragma unroll
-  for (int rr = 0; rr < R; rr++)
+  for (int rr = 0; rr < NV; rr++)
     st.lacc[rr] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[rr], st.lacc[rr], 0, 0, 0);
 #pragma unroll
   for (int dt = 0; dt < 8; dt++) {
-    bf16x4 va[2];
+    const bf16x8 a = __builtin_shufflevector(va[dt][0], va[dt][1], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-    for (int t = 0; t < 2; t++) {
-      const int row = 16 * t + 4 * kg + (c >> 2);
-      const int piece = 2 * dt + ((c & 3) >> 1);
-      const int slot = piece ^ ((row & 7) << 1);
-      const char* addr = vbytes + row * 256 + slot * 16 + (c & 1) * 8;
-      va[t] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(addr));
-    }
-    const bf16x8 a = __builtin_shufflevector(va[0], va[1], 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-    for (int rr = 0; rr < R; rr++)
+    for (int rr = 0; rr < NV; rr++)
       st.o[rr][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rr], st.o[rr][dt], 0, 0, 0);
   }
 }
@@ -239,7 +249,7 @@ __device__ __forceinline__ void pin_args(AttnParams& p) {
   CB_PIN(p.kv.seq_stride); CB_PIN(p.kv.token_stride); CB_PIN(p.kv.head_stride); CB_PIN(p.kv.num_blocks);
   CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.anc); CB_PIN(p.partial); CB_PIN(p.tickets);
   CB_PIN(p.Hq); CB_PIN(p.Hkv); CB_PIN(p.chunk); CB_PIN(p.nsplit); CB_PIN(p.batch); CB_PIN(p.scale);
-  CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags);
+  CB_PIN(p.external_merge); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags);
   CB_PIN(p.status); CB_PIN(p.dbg_ts);
 }
 #undef CB_PIN
@@ -248,7 +258,7 @@ __device__ __forceinline__ void pin_args(AttnParams& p) {
 // of DPT dims).  Partials are combined online, BS splits per batch with all of a batch's loads in
 // flight together: m = max m_t, w_t = e^(m_t - m), o = sum w_t o_t / sum w_t l_t.
 // POL is the buffer cache policy of the loads.
-template <int R, int G, int POL>
+template <int RT, int G, int POL>
 __device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_rsrc_t prsrc, int64_t seq_row0,
                                            int row0, int M, int g, int off, int hk, int nsplit_b, int tid) {
   constexpr int D = 128;
@@ -257,7 +267,7 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_
   constexpr int VPT = DPT / 8;     // 16-byte loads (8 bf16) per split and thread
   constexpr int BS = 16 / VPT;     // splits per batch
   const int slice = tid % SL;
-  for (int rl = tid / SL; rl < 64 * R; rl += 64) {
+  for (int rl = tid / SL; rl < RT; rl += 64) {
     const int row = row0 + rl;
     if (row >= M) break;
     const int node = row / g, hg = row - node * g;
@@ -318,12 +328,16 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_
 }
 
 // grid: x = split, y = kv head + Hkv * row tile, z = sequence; block = 256 * G threads.
-// G wave groups share the 64*R rows of the tile: group gi takes keys [32 gi, 32 gi + 32) of every
-// 32*G-key stage, so with G = 2 each SIMD holds two waves whose MFMA, LDS and vector phases
-// overlap; their softmax states are combined through LDS before the partial is written.
-template <int R, int G>
+// A ring stage holds 32*G keys.  With SEQ = false the G wave groups share the 64*R rows of the tile
+// and group gi takes keys [32 gi, 32 gi + 32) of every stage (short of rows, long on keys: each SIMD
+// still holds two waves whose MFMA, LDS and vector phases overlap; the groups' softmax states are
+// combined through LDS at the end).  With SEQ = true every wave owns its own 16*R rows -- the tile
+// has 64*R*G rows -- and walks through all G key halves of a stage itself, so K/V is read from HBM
+// once for a tile of up to 256 rows.
+template <int R, int G, bool SEQ>
 __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta meta) {
-  static_assert(G == 1 || (G == 2 && R == 1), "two wave groups are only built for one row tile per wave");
+  static_assert(G == 1 || (G == 2 && R <= 2), "two wave groups are built for one or two row tiles per wave");
+  constexpr int RT = 64 * R * (SEQ ? G : 1);  // rows of the workgroup's tile
   // All kernel arguments are fetched in one burst at entry (see pin_args): left to itself the
   // compiler loads each near its first use, behind early exits, and the chain of dependent scalar
   // loads then costs several microseconds before the first K/V request goes out.
@@ -344,7 +358,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   __shared__ uint4 K0[SV], K1[SV], K2[SV], K3[SV];  // one object per ring slot: the compiler tracks
   __shared__ uint4 V0[SV], V1[SV], V2[SV], V3[SV];  // LDS-DMA completion per object
   __shared__ int bt_lds[kMaxBtLds];
-  __shared__ uint32_t anc_lds[64 * R * kAncWords];
+  __shared__ uint32_t anc_lds[RT * kAncWords];
   __shared__ int last_flag;
   constexpr int D = 128;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
@@ -375,7 +389,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   CB_TS(1);
   const int off = shp.off, N = shp.N, S = shp.S;
   const int M = N * g;
-  const int row0 = rt * 64 * R;
+  const int row0 = rt * RT;
   if (row0 >= M) return;
   const int len = S + N;
   const int k0 = split * p.chunk;
@@ -404,9 +418,11 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   WaveState<R> st;
   int row_local[R];   // row index inside the workgroup's tile (for anc_lds)
   int64_t grow[R];    // global output row (node * Hq + head), or -1 past the end
+  int nvt = 0;        // this wave's row tiles that hold at least one real row (they come first)
 #pragma unroll
   for (int rr = 0; rr < R; rr++) {
-    const int rl = (wi * R + rr) * 16 + c;
+    const int rl = ((SEQ ? w : wi) * R + rr) * 16 + c;
+    if (row0 + rl - c < M) nvt = rr + 1;
     int row = row0 + rl;
     const bool valid = row < M;
     row = valid ? row : M - 1;
@@ -423,7 +439,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     st.mref[rr] = -INFINITY;
   }
   const bool tree_split = k1 > S;  // this split reaches the tree nodes: masks needed
-  constexpr int kAncPerThread = (64 * R * kAncWords + NT - 1) / NT;
+  constexpr int kAncPerThread = (RT * kAncWords + NT - 1) / NT;
   uint32_t ancv[kAncPerThread];
   if (tree_split) {
 #pragma unroll
@@ -431,7 +447,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
       const int idx = tid + i * NT;
       int row = row0 + idx / kAncWords;
       row = row < M ? row : M - 1;
-      ancv[i] = (idx < 64 * R * kAncWords) ? ganc[(int64_t)(off + row / g) * kAncWords + (idx % kAncWords)] : 0u;
+      ancv[i] = (idx < RT * kAncWords) ? ganc[(int64_t)(off + row / g) * kAncWords + (idx % kAncWords)] : 0u;
     }
   }
 
@@ -449,11 +465,17 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
 #pragma unroll
     for (int i = 0; i < kAncPerThread; i++) {
       const int idx = tid + i * NT;
-      if (idx < 64 * R * kAncWords) anc_lds[idx] = ancv[i];
+      if (idx < RT * kAncWords) anc_lds[idx] = ancv[i];
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // written before the first ring barrier below
   }
 
+// the row tiles of a wave that lie past the sequence's rows are left out (R = 2: all, one or none)
+#define CB_COMPUTE(kp, vp, key0, need_mask)                                                                    \
+  do {                                                                                                         \
+    if (nvt == R) compute_stage<R, R>(kp, vp, st, c2, key0, S, k1, need_mask, anc_lds, row_local, l);          \
+    else if (R > 1) compute_stage<R, 1>(kp, vp, st, c2, key0, S, k1, need_mask, anc_lds, row_local, l);        \
+  } while (0)
 #define CB_STAGE(J, JPREV)                                                                         \
   {                                                                                                \
     const int s = s0 + J;                                                                          \
@@ -463,11 +485,12 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
       ring_barrier();                                                                              \
       if (s == 0) CB_TS(3);                                                                        \
       if (s + NS - 1 < nst && !(p.debug_flags & 4)) CB_ISSUE(JPREV, s + NS - 1);                   \
-      const int key0 = k0 + s * SK + gi * kStageKeys;                                              \
-      const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                      \
-      if (key0 < k1 && !(p.debug_flags & 2))                                                       \
-        compute_stage<R>(K##J + gi * kStageVecs, V##J + gi * kStageVecs, st, c2, key0, S, k1,      \
-                         need_mask, anc_lds, row_local, l);                                        \
+      _Pragma("unroll") for (int h = SEQ ? 0 : gi; h < (SEQ ? G : gi + 1); h++) {                  \
+        const int key0 = k0 + s * SK + h * kStageKeys;                                             \
+        const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                    \
+        if (key0 < k1 && nvt > 0 && !(p.debug_flags & 2))                                          \
+          CB_COMPUTE(K##J + h * kStageVecs, V##J + h * kStageVecs, key0, need_mask);               \
+      }                                                                                            \
     }                                                                                              \
   }
   for (int s0 = 0; s0 < nst; s0 += NS) {
@@ -477,38 +500,46 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     CB_STAGE(3, 2)
   }
 #undef CB_STAGE
+#undef CB_COMPUTE
 #undef CB_ISSUE
 
   CB_TS(4);
   if (p.debug_flags & 8) return;  // (timing aid: stop after the key sweep)
 
-  if constexpr (G == 2) {
+  if constexpr (G == 2 && !SEQ) {
     // combine the two wave groups' softmax states: group 1 parks (o, mref, l) in the ring, group 0 adds it
     __syncthreads();  // every wave is done with the ring
     const int lane = wi * 64 + l;
+    uint4* const park[4] = {K0, K1, K2, K3};  // 4 accumulator tiles x 256 lanes x 16 B each
+    float2* const park_ml = reinterpret_cast<float2*>(V0);
     if (gi == 1) {
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
-        K0[dt * 256 + lane] = __builtin_bit_cast(uint4, st.o[0][dt]);
-        K1[dt * 256 + lane] = __builtin_bit_cast(uint4, st.o[0][dt + 4]);
+      for (int rr = 0; rr < R; rr++) {
+#pragma unroll
+        for (int dt = 0; dt < 8; dt++) {
+          const int slot = rr * 8 + dt;
+          park[slot >> 2][(slot & 3) * 256 + lane] = __builtin_bit_cast(uint4, st.o[rr][dt]);
+        }
+        park_ml[rr * 256 + lane] = float2{st.mref[rr], st.lacc[rr][0]};
       }
-      reinterpret_cast<float2*>(V0)[lane] = float2{st.mref[0], st.lacc[0][0]};
     }
     __syncthreads();
     if (gi == 0) {
-      const float2 ml = reinterpret_cast<const float2*>(V0)[lane];
-      const float m = fmaxf(st.mref[0], ml.x);
-      const float mu = (m == -INFINITY) ? 0.f : m;
-      const float w0 = __builtin_amdgcn_exp2f((st.mref[0] - mu) * c2), w1 = __builtin_amdgcn_exp2f((ml.x - mu) * c2);
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
-        const floatx4 a = __builtin_bit_cast(floatx4, K0[dt * 256 + lane]);
-        const floatx4 bq = __builtin_bit_cast(floatx4, K1[dt * 256 + lane]);
-        st.o[0][dt] = st.o[0][dt] * w0 + a * w1;
-        st.o[0][dt + 4] = st.o[0][dt + 4] * w0 + bq * w1;
+      for (int rr = 0; rr < R; rr++) {
+        const float2 ml = park_ml[rr * 256 + lane];
+        const float m = fmaxf(st.mref[rr], ml.x);
+        const float mu = (m == -INFINITY) ? 0.f : m;
+        const float w0 = __builtin_amdgcn_exp2f((st.mref[rr] - mu) * c2), w1 = __builtin_amdgcn_exp2f((ml.x - mu) * c2);
+#pragma unroll
+        for (int dt = 0; dt < 8; dt++) {
+          const int slot = rr * 8 + dt;
+          const floatx4 a = __builtin_bit_cast(floatx4, park[slot >> 2][(slot & 3) * 256 + lane]);
+          st.o[rr][dt] = st.o[rr][dt] * w0 + a * w1;
+        }
+        st.lacc[rr][0] = st.lacc[rr][0] * w0 + ml.y * w1;
+        st.mref[rr] = m;
       }
-      st.lacc[0][0] = st.lacc[0][0] * w0 + ml.y * w1;
-      st.mref[0] = m;
     }
   }
 
@@ -517,7 +548,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
       reinterpret_cast<char*>(p.partial) + seq_row0 * p.nsplit * kPartialBytes, 0, 0x7fffffff, 0x00020000);
   // finish.  Every lane holds its query's full denominator.
-  if (gi == 0) {
+  if (SEQ || gi == 0) {
 #pragma unroll
     for (int rr = 0; rr < R; rr++) {
       const float lt = st.lacc[rr][0];
@@ -540,18 +571,20 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
         for (int dt = 0; dt < 8; dt++) {
           const uintx2 v = {(uint32_t)f2bf(st.o[rr][dt][0]) | ((uint32_t)f2bf(st.o[rr][dt][1]) << 16),
                             (uint32_t)f2bf(st.o[rr][dt][2]) | ((uint32_t)f2bf(st.o[rr][dt][3]) << 16)};
-          __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, kAgentCoherent);
+          if (p.external_merge) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, 0);
+          else __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, kAgentCoherent);
         }
         if (kg == 0) {
           // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
           const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
           const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
-          __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, kAgentCoherent);
+          if (p.external_merge) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, 0);
+          else __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, kAgentCoherent);
         }
       }
     }
   }
-  if (nsplit_b == 1) return;
+  if (nsplit_b == 1 || p.external_merge) return;  // (a following kernel merges: the kernel boundary orders the stores)
 
   // ---- split merge by the last workgroup of this (sequence, kv head, row tile) to finish.
   // The partials above are write-through stores; once they have completed (vmcnt 0) the workgroup
@@ -589,11 +622,72 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   if (!last_flag) return;
   // Same XCD: the write-through stores left the lines in this L2, plain (cached) loads are coherent
   // with them.  Otherwise read past the L2 with agent-coherent loads.
-  if (last_flag == 1) merge_rows<R, G, 0>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
-  else merge_rows<R, G, kAgentCoherent>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
+  if (last_flag == 1) merge_rows<RT, G, 0>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
+  else merge_rows<RT, G, kAgentCoherent>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   CB_TS(7);
 #undef CB_TS
+}
+
+// Stand-alone merge of the bf16 partials, used when a tile's partials are too many for one
+// workgroup to pull through its compute unit: 16 rows per workgroup, thread -> (row, 8-dim slice).
+__global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMeta meta, int total_rows) {
+  constexpr int D = 128;
+  const int tid = threadIdx.x;
+  const int64_t gr = (int64_t)blockIdx.x * 16 + (tid >> 4);
+  if (gr >= total_rows) return;
+  const int slice = tid & 15;
+  const int node = (int)(gr / p.Hq);
+  int b = 0;
+  while (b + 1 < p.batch && node >= meta.node_off[b + 1]) b++;
+  const int len = meta.kv_len[b] + (meta.node_off[b + 1] - meta.node_off[b]);
+  const int ns = (len + p.chunk - 1) / p.chunk;
+  if (ns <= 1) return;  // the attention kernel already wrote the output
+  const char* pr = reinterpret_cast<const char*>(p.partial) + gr * p.nsplit * kPartialBytes;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++) acc[i] = 0.f;
+  float lsum = 0.f, m_run = -INFINITY;
+  constexpr int BS = 8;
+  for (int t0 = 0; t0 < ns; t0 += BS) {
+    uint4 v[BS];
+    float2 ml[BS];
+#pragma unroll
+    for (int u = 0; u < BS; u++) {
+      const int t = (t0 + u < ns) ? t0 + u : ns - 1;
+      const char* tb = pr + (int64_t)t * kPartialBytes;
+      ml[u] = *reinterpret_cast<const float2*>(tb + D * 2);
+      v[u] = *reinterpret_cast<const uint4*>(tb + slice * 16);
+    }
+    float mb = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < BS; u++)
+      if (t0 + u < ns) mb = fmaxf(mb, ml[u].x);
+    const float m_new = fmaxf(m_run, mb);
+    const float resc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] *= resc;
+    lsum *= resc;
+    m_run = m_new;
+#pragma unroll
+    for (int u = 0; u < BS; u++) {
+      const float wgt = (t0 + u < ns && ml[u].x != -INFINITY) ? __expf(ml[u].x - m_new) : 0.f;
+      lsum = fmaf(ml[u].y, wgt, lsum);
+      const uint32_t wv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        acc[2 * k] = fmaf(__uint_as_float(wv[k] << 16), wgt, acc[2 * k]);
+        acc[2 * k + 1] = fmaf(__uint_as_float(wv[k] & 0xffff0000u), wgt, acc[2 * k + 1]);
+      }
+    }
+  }
+  const float inv = 1.0f / lsum;
+  uint4 pk;
+  pk.x = (uint32_t)f2bf(acc[0] * inv) | ((uint32_t)f2bf(acc[1] * inv) << 16);
+  pk.y = (uint32_t)f2bf(acc[2] * inv) | ((uint32_t)f2bf(acc[3] * inv) << 16);
+  pk.z = (uint32_t)f2bf(acc[4] * inv) | ((uint32_t)f2bf(acc[5] * inv) << 16);
+  pk.w = (uint32_t)f2bf(acc[6] * inv) | ((uint32_t)f2bf(acc[7] * inv) << 16);
+  *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(p.out) + gr * D + slice * 8) = pk;
 }
 
 bool attn_mfma_supports(const AttnParams& p) {
@@ -608,12 +702,19 @@ bool attn_mfma_supports(const AttnParams& p) {
   return true;
 }
 
-hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call) {
+// Rows per workgroup tile the launcher picks for a call whose largest sequence has `mrows` rows
+// (g query heads x N nodes) per kv head.
+int attn_mfma_tile_rows(int mrows) { return mrows <= 64 ? 64 : (mrows <= 128 ? 128 : 256); }
+
+hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
+                            int total_nodes) {
   if (!attn_mfma_supports(p)) return hipErrorInvalidValue;
   const int g = p.Hq / p.Hkv;
   const int M = max_nodes_in_call * g;
-  const int R = M <= 64 ? 1 : (M <= 128 ? 2 : 4);
-  const int tiles = (M + 64 * R - 1) / (64 * R);
+  int rt_rows = attn_mfma_tile_rows(M);
+  if ((p.debug_flags & 64) && rt_rows > 128) rt_rows = 128;  // (timing aids: smaller row tiles)
+  if (p.debug_flags & 128) rt_rows = 64;
+  const int tiles = (M + rt_rows - 1) / rt_rows;
   dim3 grid(p.nsplit, p.Hkv * tiles, p.batch);
   AttnParams q = p;
   const int64_t T = (int64_t)p.nsplit * p.Hkv * tiles * p.batch;
@@ -622,12 +723,21 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   q.grid_x = grid.x;
   q.grid_y = grid.y;
   q.grid_z = grid.z;
-  const bool one_group = (p.debug_flags & 16) != 0;  // (timing aid: 4-wave variant for one row tile)
-  if (R == 1 && !one_group) hipLaunchKernelGGL((k_attn_mfma<1, 2>), grid, dim3(512), 0, st, q, meta);
-  else if (R == 1) hipLaunchKernelGGL((k_attn_mfma<1, 1>), grid, dim3(256), 0, st, q, meta);
-  else if (R == 2) hipLaunchKernelGGL((k_attn_mfma<2, 1>), grid, dim3(256), 0, st, q, meta);
-  else hipLaunchKernelGGL((k_attn_mfma<4, 1>), grid, dim3(256), 0, st, q, meta);
-  return hipGetLastError();
+  // one workgroup can pull about 50 GB/s of partials through its compute unit: beyond a few hundred
+  // KiB per tile a separate, fully parallel merge kernel is cheaper than the in-kernel merge
+  q.external_merge = (p.nsplit > 1 && (int64_t)p.nsplit * rt_rows * kPartialBytes > 320 * 1024) ? 1 : 0;
+  if (p.debug_flags & 256) q.external_merge = 1;  // (timing aid)
+  if (rt_rows == 64) hipLaunchKernelGGL((k_attn_mfma<1, 2, false>), grid, dim3(512), 0, st, q, meta);
+  else if (rt_rows == 128) hipLaunchKernelGGL((k_attn_mfma<2, 2, false>), grid, dim3(512), 0, st, q, meta);
+  else hipLaunchKernelGGL((k_attn_mfma<2, 2, true>), grid, dim3(512), 0, st, q, meta);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (q.external_merge && !(p.debug_flags & 1)) {
+    const int total_rows = total_nodes * p.Hq;
+    hipLaunchKernelGGL(k_merge_partials_bf16, dim3((total_rows + 15) / 16), dim3(256), 0, st, q, meta, total_rows);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 }  // namespace cb

@@ -84,6 +84,7 @@ struct AttnParams {
   float scale;
   int32_t xcd_remap;    // 1: renumber workgroups so that all splits of a tile run on one XCD
   int32_t grid_x, grid_y, grid_z;  // launch grid, repeated here so the kernel reads one argument block
+  int32_t external_merge;  // 1: the kernel only writes partials; launch_attn_mfma runs a merge kernel afterwards
   int32_t debug_flags;  // bit 0: skip the split merge (timing aid; output then undefined)
   int32_t* status;      // device status word (bit 4: a merge had to use cross-XCD loads)
   unsigned long long* dbg_ts;  // timing aid: 8 timestamps (100 MHz) per workgroup when debug bit 5 is set
@@ -109,7 +110,9 @@ hipError_t launch_compact(hipStream_t st, int batch, const SeqMeta& meta, const 
 hipError_t launch_attn_simt(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype,
                             int max_nodes_in_call);
 hipError_t launch_merge(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype, int total_nodes);
+int attn_mfma_tile_rows(int mrows);            // rows per workgroup tile chosen for a given g*N
 bool attn_mfma_supports(const AttnParams& p);  // shape/geometry the MFMA kernel takes (bf16 is the caller's check)
-hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call);
+hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
+                            int total_nodes);
 
 }  // namespace cb
