@@ -261,9 +261,21 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.debug_flags = (int32_t)ctx->opt_debug;
 
   const int64_t stages = ctx->opt_stages;  // measurement aid: bit 0 prepare, 1 attention, 2 argmax, 3 acceptance
-  if (stages & 1)
-    CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
-                                    ctx->dev<int32_t>(ctx->lay.status)));
+  // The logits scan does not depend on the attention, so it goes first and carries the ancestor-set
+  // blocks with it (one launch fewer); the attention and the acceptance follow.
+  if ((stages & 1) && (stages & 4)) {
+    CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
+                              ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
+                              d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc), ctx->dev<int32_t>(ctx->lay.status)));
+  } else {
+    if (stages & 1)
+      CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
+                                      ctx->dev<int32_t>(ctx->lay.status)));
+    if (stages & 4)
+      CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
+                                ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
+                                nullptr, c.max_depth, nullptr, nullptr));
+  }
   const bool timing = ctx->opt_time != 0;
   if (timing) CB_HIP(ctx, hipEventRecord(ctx->ev0, st));
   if (!(stages & 2)) {
@@ -277,9 +289,6 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
     CB_HIP(ctx, hipEventRecord(ctx->ev1, st));
     ctx->ev_valid = true;
   }
-  if (stages & 4)
-    CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
-                              ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks));
   if (stages & 8)
     CB_HIP(ctx, launch_accept(st, batch, meta, d_parent, d_tokens, ctx->dev<uint32_t>(ctx->lay.anc),
                             ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, c.max_depth,

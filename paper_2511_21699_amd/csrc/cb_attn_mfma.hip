@@ -455,9 +455,13 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   const int last_key = len - 1;
 
 #define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * SK, last_key, w, l)
+  const bool fine_ts = (p.debug_flags & 1024) != 0;  // (timing aid: slots 5-7 stamp the issue phase instead)
+  if (fine_ts) CB_TS(5);
   if (!(p.debug_flags & 4)) {  // (timing aid: bit 2 leaves the loads out, bit 1 the arithmetic)
     if (0 < nst) CB_ISSUE(0, 0);
+    if (fine_ts) CB_TS(6);
     if (1 < nst) CB_ISSUE(1, 1);
+    if (fine_ts) CB_TS(7);
     if (2 < nst) CB_ISSUE(2, 2);
   }
   CB_TS(2);
@@ -571,14 +575,14 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
         for (int dt = 0; dt < 8; dt++) {
           const uintx2 v = {(uint32_t)f2bf(st.o[rr][dt][0]) | ((uint32_t)f2bf(st.o[rr][dt][1]) << 16),
                             (uint32_t)f2bf(st.o[rr][dt][2]) | ((uint32_t)f2bf(st.o[rr][dt][3]) << 16)};
-          if (p.external_merge) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, 0);
+          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, 0);
           else __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, kAgentCoherent);
         }
         if (kg == 0) {
           // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
           const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
           const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
-          if (p.external_merge) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, 0);
+          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, 0);
           else __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, kAgentCoherent);
         }
       }

@@ -98,8 +98,10 @@ struct ArgmaxPartial {
 // ---- launchers (defined in the .hip files); all enqueue on `st` and return the launch status
 hipError_t launch_tree_prepare(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
                                int max_depth, uint32_t* anc, int32_t* status);
+// scans the logits; with prep_parent != nullptr the same launch also builds the ancestor sets
 hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows, int64_t V,
-                         ArgmaxPartial* partial, int nchunks);
+                         ArgmaxPartial* partial, int nchunks, int batch, const SeqMeta& meta,
+                         const int32_t* prep_parent, int max_depth, uint32_t* prep_anc, int32_t* status);
 hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
                          const int32_t* tokens, const uint32_t* anc, const ArgmaxPartial* partial,
                          int nchunks, int max_depth, int32_t* argmax_out, int32_t* path,

@@ -23,12 +23,17 @@ __device__ __forceinline__ int sanitized_parent(const int32_t* parent, int off, 
   return p;
 }
 
-__global__ __launch_bounds__(256) void k_tree_prepare(SeqMeta meta, const int32_t* __restrict__ parent,
-                                                      int max_depth, uint32_t* __restrict__ anc,
-                                                      int32_t* status) {
-  __shared__ uint32_t A[2][CB_MAX_NODES][kAncWords];
-  __shared__ int J[2][CB_MAX_NODES];
-  const int b = blockIdx.x, t = threadIdx.x;
+struct PrepareLds {
+  uint32_t A[2][CB_MAX_NODES][kAncWords];
+  int J[2][CB_MAX_NODES];
+};
+
+__device__ __forceinline__ void tree_prepare_block(PrepareLds& sh, const SeqMeta& meta, int b,
+                                                   const int32_t* __restrict__ parent, int max_depth,
+                                                   uint32_t* __restrict__ anc, int32_t* status) {
+  auto& A = sh.A;
+  auto& J = sh.J;
+  const int t = threadIdx.x;
   const int off = meta.node_off[b];
   int N = meta.node_off[b + 1] - off;
   N = N > CB_MAX_NODES ? CB_MAX_NODES : N;
@@ -58,6 +63,13 @@ __global__ __launch_bounds__(256) void k_tree_prepare(SeqMeta meta, const int32_
   }
 }
 
+__global__ __launch_bounds__(256) void k_tree_prepare(SeqMeta meta, const int32_t* __restrict__ parent,
+                                                      int max_depth, uint32_t* __restrict__ anc,
+                                                      int32_t* status) {
+  __shared__ PrepareLds sh;
+  tree_prepare_block(sh, meta, blockIdx.x, parent, max_depth, anc, status);
+}
+
 hipError_t launch_tree_prepare(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
                                int max_depth, uint32_t* anc, int32_t* status) {
   hipLaunchKernelGGL(k_tree_prepare, dim3(batch), dim3(256), 0, st, meta, parent, max_depth, anc, status);
@@ -77,10 +89,28 @@ __device__ __forceinline__ void amax_take(float& bv, int& bi, float v, int i) {
   if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
 }
 
+// Rows [0, rows) of the grid's y dimension scan logits; when `prep` is set, rows [rows, rows + batch)
+// build the ancestor sets of one sequence each (x = 0 only), which saves a launch of their own.
+struct PrepareArgs {
+  const int32_t* parent;
+  uint32_t* anc;
+  int32_t* status;
+  int32_t max_depth;
+  int32_t enabled;
+};
+
 template <typename T>
-__global__ __launch_bounds__(256) void k_argmax(const T* __restrict__ logits, int64_t V,
-                                                ArgmaxPartial* __restrict__ out, int nchunks) {
+__global__ __launch_bounds__(256) void k_argmax(const T* __restrict__ logits, int64_t V, int rows,
+                                                ArgmaxPartial* __restrict__ out, int nchunks, SeqMeta meta,
+                                                PrepareArgs prep) {
+  __shared__ PrepareLds prep_lds;
+  if ((int)blockIdx.y >= rows) {
+    if (blockIdx.x == 0 && prep.enabled)
+      tree_prepare_block(prep_lds, meta, blockIdx.y - rows, prep.parent, prep.max_depth, prep.anc, prep.status);
+    return;
+  }
   constexpr int VEC = 16 / sizeof(T);
+  constexpr int kVecPerThread = kArgmaxChunk / VEC / 256;
   const int row = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
   const int64_t start = (int64_t)c * kArgmaxChunk;
   const int64_t end = (start + kArgmaxChunk < V) ? start + kArgmaxChunk : V;
@@ -93,21 +123,29 @@ __global__ __launch_bounds__(256) void k_argmax(const T* __restrict__ logits, in
     const int64_t nvec = (end - start) / VEC;
     vec_end = start + nvec * VEC;
     const uint4* vp = reinterpret_cast<const uint4*>(base + start);
-    for (int64_t i = tid; i < nvec; i += 256) {
-      uint4 u = vp[i];
+    uint4 u[kVecPerThread];  // all of the thread's loads are in flight together
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; k++) {
+      const int64_t i = tid + k * 256;
+      u[k] = i < nvec ? vp[i] : uint4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; k++) {
+      const int64_t i = tid + k * 256;
+      if (i >= nvec) continue;
       const int e0 = (int)(start + i * VEC);
       if constexpr (sizeof(T) == 2) {
-        uint32_t w[4] = {u.x, u.y, u.z, u.w};
+        const uint32_t w[4] = {u[k].x, u[k].y, u[k].z, u[k].w};
 #pragma unroll
-        for (int k = 0; k < 4; k++) {
-          amax_take(bv, bi, __uint_as_float(w[k] << 16), e0 + 2 * k);
-          amax_take(bv, bi, __uint_as_float(w[k] & 0xffff0000u), e0 + 2 * k + 1);
+        for (int j = 0; j < 4; j++) {
+          amax_take(bv, bi, __uint_as_float(w[j] << 16), e0 + 2 * j);
+          amax_take(bv, bi, __uint_as_float(w[j] & 0xffff0000u), e0 + 2 * j + 1);
         }
       } else {
-        amax_take(bv, bi, __uint_as_float(u.x), e0);
-        amax_take(bv, bi, __uint_as_float(u.y), e0 + 1);
-        amax_take(bv, bi, __uint_as_float(u.z), e0 + 2);
-        amax_take(bv, bi, __uint_as_float(u.w), e0 + 3);
+        amax_take(bv, bi, __uint_as_float(u[k].x), e0);
+        amax_take(bv, bi, __uint_as_float(u[k].y), e0 + 1);
+        amax_take(bv, bi, __uint_as_float(u[k].z), e0 + 2);
+        amax_take(bv, bi, __uint_as_float(u[k].w), e0 + 3);
       }
     }
   }
@@ -133,12 +171,19 @@ __global__ __launch_bounds__(256) void k_argmax(const T* __restrict__ logits, in
 }
 
 hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows, int64_t V,
-                         ArgmaxPartial* partial, int nchunks) {
-  dim3 grid(nchunks, rows);
+                         ArgmaxPartial* partial, int nchunks, int batch, const SeqMeta& meta,
+                         const int32_t* prep_parent, int max_depth, uint32_t* prep_anc, int32_t* status) {
+  PrepareArgs prep;
+  prep.parent = prep_parent;
+  prep.anc = prep_anc;
+  prep.status = status;
+  prep.max_depth = max_depth;
+  prep.enabled = prep_parent != nullptr;
+  dim3 grid(nchunks, rows + (prep.enabled ? batch : 0));
   if (dtype == CB_BF16)
-    hipLaunchKernelGGL(k_argmax<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)logits, V, partial, nchunks);
+    hipLaunchKernelGGL(k_argmax<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)logits, V, rows, partial, nchunks, meta, prep);
   else
-    hipLaunchKernelGGL(k_argmax<float>, grid, dim3(256), 0, st, (const float*)logits, V, partial, nchunks);
+    hipLaunchKernelGGL(k_argmax<float>, grid, dim3(256), 0, st, (const float*)logits, V, rows, partial, nchunks, meta, prep);
   return hipGetLastError();
 }
 
