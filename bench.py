@@ -79,6 +79,8 @@ def main():
     def make_runner(with_compact):
         """Returns (run(n_groups), steps_per_group): one group = one step on every input copy."""
         calls = bound_calls(with_compact)
+        if len(calls) == 1:
+            calls = calls * 20          # --warm: the same buffers 20 times per graph, so replay overhead stays small
         if args.no_graph:
             def run(n):
                 for _ in range(n):

@@ -18,27 +18,35 @@ _LIB_PATH = os.path.join(_HERE, "libcb_oracle.so")
 _lib = None
 
 
+def _configure(L):
+    L.cbo_num_threads.restype = C.c_int
+    L.cbo_attention_rows.restype = C.c_int
+    L.cbo_attention_rows.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_int]
+    L.cbo_argmax.restype = None
+    L.cbo_argmax.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
+    L.cbo_accept.restype = C.c_int
+    L.cbo_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+    L.cbo_compact.restype = C.c_int
+    L.cbo_compact.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
+                              C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
+    return L
+
+
+def load_library(path: str):
+    """Open an oracle shared object (the tests also load deliberately broken builds this way)."""
+    return _configure(C.CDLL(path))
+
+
 def lib():
     global _lib
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             from . import build as _b
             _b.build()
-        L = C.CDLL(_LIB_PATH)
-        L.cbo_num_threads.restype = C.c_int
-        L.cbo_attention_rows.restype = C.c_int
-        L.cbo_attention_rows.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64,
-                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
-                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_int,
-                                         C.c_void_p, C.c_void_p, C.c_int]
-        L.cbo_argmax.restype = None
-        L.cbo_argmax.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
-        L.cbo_accept.restype = C.c_int
-        L.cbo_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
-        L.cbo_compact.restype = C.c_int
-        L.cbo_compact.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
-                                  C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
-        _lib = L
+        _lib = load_library(_LIB_PATH)
     return _lib
 
 

@@ -175,9 +175,10 @@ Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const i
   if (ctx->opt_splits > 0) {
     nsplit = (int)std::min<int64_t>(ctx->opt_splits, max_splits);
   } else if (p.impl == 1) {
-    // one workgroup per (row, split): aim for a few workgroups per compute unit, splits of >= 256 keys
+    // one workgroup per (row, split): aim for a few workgroups per compute unit, but never split
+    // below 1024 keys -- a second (merge) launch costs more than a short row does
     const int64_t want = 2048;
-    nsplit = (int)std::max<int64_t>(1, std::min<int64_t>((want + rows - 1) / rows, (p.max_len + 255) / 256));
+    nsplit = (int)std::max<int64_t>(1, std::min<int64_t>((want + rows - 1) / rows, p.max_len / 1024));
   } else {
     // one workgroup per (row tile of 64, 128 or 256 rows, kv head, split)
     const int g = c.num_q_heads / c.num_kv_heads;

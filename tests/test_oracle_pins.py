@@ -207,7 +207,8 @@ def test_acceptance_equals_sequential_greedy_walk(seed):
     rng = np.random.default_rng(seed)
     n = int(rng.integers(1, 40))
     parent, depth = W.random_tree(rng, n, 3, 6, False)
-    V = 4                                                  # tiny vocabulary: many matches and duplicate siblings
+    V = 2 if seed % 2 else 4                               # tiny vocabularies: many matches; with 2 tokens siblings
+                                                           # often carry the same one, so equal-depth ties occur
     tok = rng.integers(0, V, size=n)
     a = rng.integers(0, V, size=n)
     L, path, emitted = O.accept(parent, tok, a)
