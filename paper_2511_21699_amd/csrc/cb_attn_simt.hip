@@ -116,9 +116,18 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnParams p, SeqMeta meta) {
     const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
     l_run = l_run * alpha + l_tile;
     acc *= alpha;
-    for (int jj = slice; jj < tl; jj += NS) {
-      const float e = ss[jj];
-      if (e != 0.f) acc = fmaf(e, ld_elem(vbase + slot_offset(p.kv, b, t0 + jj, hk) + d), acc);
+    // eight independent V loads in flight per thread (masked keys carry weight 0 and read slot t0)
+    for (int j0 = slice; j0 < tl; j0 += 8 * NS) {
+      float e[8], x[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int jj = j0 + u * NS;
+        e[u] = jj < tl ? ss[jj] : 0.f;
+        const int key = (e[u] != 0.f) ? t0 + jj : t0;
+        x[u] = ld_elem(vbase + slot_offset(p.kv, b, key, hk) + d);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) acc = fmaf(e[u], x[u], acc);
     }
     m_run = m_new;
     __syncthreads();

@@ -193,3 +193,46 @@ def test_error_paths_leave_outputs_alone():
         ver.verify_tree(dc.q, dc.kv, [10 + 100], case.node_offsets, case.parent, case.tokens, dc.logits)
     assert e.value.code == B.CB_ECAP
     ver.close()
+
+
+def test_hip_graph_replays_match_eager_steps():
+    """The benchmark replays captured steps: every replay of verify + compact must leave exactly what
+    the same steps leave when launched eagerly (compaction rewrites tree slots, so the state evolves)."""
+    import torch
+    case = W.make_config(2, S=700)
+    cfg = B.config_for_case(case)
+    results = {}
+    for mode in ("eager", "graph"):
+        dc = B.DeviceCase(case)
+        ver = B.Verifier(cfg)
+        d_par = torch.from_numpy(case.parent).cuda(); d_tok = torch.from_numpy(case.tokens).cuda()
+        out = torch.zeros_like(dc.q)
+        d_len = torch.zeros(1, dtype=torch.int32, device="cuda")
+        d_acc = torch.zeros(1, case.max_depth + 1, dtype=torch.int32, device="cuda")
+        side = torch.cuda.Stream()
+        step = ver.bind_step(dc.q, dc.kv, case.kv_len, case.node_offsets, d_par, d_tok, dc.logits, out, d_len, d_acc,
+                             [dc.kv], stream=side)
+        snaps = []
+        if mode == "graph":
+            with torch.cuda.stream(side):
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+        for rep in range(3):
+            with torch.cuda.stream(side):
+                if mode == "graph":
+                    graph.replay()
+                else:
+                    step()
+            side.synchronize()
+            # eager work of the program's own between the replays
+            scratch = (dc.logits.float().sum() + out.float().abs().sum()).item()
+            assert np.isfinite(scratch)
+            snaps.append((B.to_host(out, "bf16").copy(), B.to_host(dc.k, "bf16").copy(), B.to_host(dc.v, "bf16").copy(),
+                          d_len.cpu().numpy().copy(), d_acc.cpu().numpy().copy()))
+        results[mode] = snaps
+        ver.close()
+    for rep in range(3):
+        for a, b in zip(results["eager"][rep], results["graph"][rep]):
+            assert np.array_equal(a, b), f"replay {rep} differs from the eager step"
+    assert results["eager"][0][3][0] >= 0
