@@ -173,6 +173,7 @@ int cb_device_status(cb_ctx *ctx, int32_t *status);
  *   "stages"     bit mask of the steps cb_verify_tree_device enqueues (1 ancestor sets, 2 attention,
  *                4 argmax, 8 acceptance; default 15) -- for timing one step in isolation; with a
  *                step left out the results of the call are those of an earlier call or undefined
+ *   "parallel_scan"  1 = run the logits scan on the context's second stream beside the attention
  *   "time_attention"  1 = record HIP events around the attention kernels (see cb_last_attention_ms) */
 int cb_set_option(cb_ctx *ctx, const char *name, int64_t value);
 

@@ -103,8 +103,9 @@ struct cb_ctx {
   int32_t last_len[CB_MAX_BATCH];
   hipStream_t last_stream;
   // options
-  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug;
-  hipEvent_t ev0, ev1;
+  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug, opt_fork;
+  hipEvent_t ev0, ev1, ev_fork, ev_join;
+  hipStream_t aux;  // second stream (default priority) for the logits scan beside the attention
   bool ev_valid;
   char err[256];
 
@@ -248,6 +249,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.out = attn_out;
   if (!make_kv_addr(c, *kv, &ap.kv)) return set_err(ctx, CB_EINVAL, "unknown cache layout %d", kv->layout);
   ap.anc = ctx->dev<uint32_t>(ctx->lay.anc);
+  ap.parent = d_parent;
   ap.partial = ctx->dev<float>(ctx->lay.partial);
   ap.tickets = ctx->dev<uint32_t>(ctx->lay.tickets);
   ap.Hq = c.num_q_heads;
@@ -261,26 +263,36 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.dbg_ts = ctx->dev<unsigned long long>(ctx->lay.dbg);
   ap.debug_flags = (int32_t)ctx->opt_debug;
 
-  const int64_t stages = ctx->opt_stages;  // measurement aid: bit 0 prepare, 1 attention, 2 argmax, 3 acceptance
-  // The logits scan does not depend on the attention, so it goes first and carries the ancestor-set
-  // blocks with it (one launch fewer); the attention and the acceptance follow.
-  if ((stages & 1) && (stages & 4)) {
-    CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
-                              ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
-                              d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc), ctx->dev<int32_t>(ctx->lay.status)));
-  } else {
-    if (stages & 1)
-      CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
-                                      ctx->dev<int32_t>(ctx->lay.status)));
-    if (stages & 4)
-      CB_HIP(ctx, launch_argmax(st, logits, c.logits_dtype, total, c.vocab_size,
-                                ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
-                                nullptr, c.max_depth, nullptr, nullptr));
+  const int64_t stages = ctx->opt_stages;  // measurement aid: bit 0 ancestor sets, 1 attention, 2 argmax, 3 acceptance
+  const bool use_mfma = plan.impl == 2 && attn_mfma_supports(ap);
+  // The logits scan does not depend on the attention, and the MFMA attention builds the ancestor sets
+  // it needs itself, so with option "parallel_scan" the scan runs beside it on the context's second
+  // stream (fork/join with events; stream capture turns them into parallel graph branches).  Measured
+  // on the 7B shape the cross-stream edges cost more than the 5 us scan they hide, so it is off by
+  // default.  The scalar attention reads the sets from the workspace: there the scan goes first and
+  // carries the blocks that build them.
+  const bool fork = ctx->opt_fork != 0 && use_mfma && (stages & 2) && (stages & 4);
+  hipStream_t scan_stream = st;
+  if (fork) {
+    CB_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+    CB_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0));
+    scan_stream = ctx->aux;
   }
+  if (stages & 4) {
+    const bool carry = !use_mfma && (stages & 1);
+    CB_HIP(ctx, launch_argmax(scan_stream, logits, c.logits_dtype, total, c.vocab_size,
+                              ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
+                              carry ? d_parent : nullptr, c.max_depth, carry ? ctx->dev<uint32_t>(ctx->lay.anc) : nullptr,
+                              carry ? ctx->dev<int32_t>(ctx->lay.status) : nullptr));
+  } else if (!use_mfma && (stages & 1)) {
+    CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
+                                    ctx->dev<int32_t>(ctx->lay.status)));
+  }
+  if (fork) CB_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux));
   const bool timing = ctx->opt_time != 0;
   if (timing) CB_HIP(ctx, hipEventRecord(ctx->ev0, st));
   if (!(stages & 2)) {
-  } else if (plan.impl == 2 && attn_mfma_supports(ap)) {
+  } else if (use_mfma) {
     CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total));  // merges its own splits
   } else {
     CB_HIP(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
@@ -290,11 +302,12 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
     CB_HIP(ctx, hipEventRecord(ctx->ev1, st));
     ctx->ev_valid = true;
   }
+  if (fork) CB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
   if (stages & 8)
-    CB_HIP(ctx, launch_accept(st, batch, meta, d_parent, d_tokens, ctx->dev<uint32_t>(ctx->lay.anc),
-                            ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, c.max_depth,
-                            ctx->dev<int32_t>(ctx->lay.amax_out), ctx->dev<int32_t>(ctx->lay.path),
-                            ctx->dev<int32_t>(ctx->lay.len_ctx), d_len, d_tok));
+    CB_HIP(ctx, launch_accept(st, batch, meta, d_parent, d_tokens, ctx->dev<int32_t>(ctx->lay.status),
+                              ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, c.max_depth,
+                              ctx->dev<int32_t>(ctx->lay.amax_out), ctx->dev<int32_t>(ctx->lay.path),
+                              ctx->dev<int32_t>(ctx->lay.len_ctx), d_len, d_tok));
   ctx->meta = meta;
   ctx->batch = batch;
   ctx->total_nodes = total;
@@ -392,6 +405,9 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   ctx->h_misc = h;
   e = hipEventCreate(&ctx->ev0);
   if (e == hipSuccess) e = hipEventCreate(&ctx->ev1);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipMemset(ctx->ws + lay.status, 0, 4);
   if (e == hipSuccess) e = hipMemset(ctx->ws + lay.tickets, 0, (size_t)lay.ticket_count * 4);
   if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -539,6 +555,7 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   else if (!strcmp(name, "time_attention")) ctx->opt_time = value;
   else if (!strcmp(name, "stages")) ctx->opt_stages = value & 15;
   else if (!strcmp(name, "debug_flags")) ctx->opt_debug = value;
+  else if (!strcmp(name, "parallel_scan")) ctx->opt_fork = value;
   else return set_err(ctx, CB_EINVAL, "unknown option '%s'", name);
   return CB_OK;
 }
@@ -565,6 +582,9 @@ void cb_destroy(cb_ctx* ctx) {
   if (!ctx) return;
   (void)hipEventDestroy(ctx->ev0);
   (void)hipEventDestroy(ctx->ev1);
+  (void)hipEventDestroy(ctx->ev_fork);
+  (void)hipEventDestroy(ctx->ev_join);
+  (void)hipStreamDestroy(ctx->aux);
   (void)hipHostFree(ctx->h_block);
   delete ctx;
 }

@@ -150,10 +150,12 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
 #pragma unroll
     for (int ds = 0; ds < 4; ds++) kraw[sub][ds] = ks[row * 16 + ((kg + 4 * ds) ^ (row & 15))];
   }
+  // (with one row tile per wave the V operands are also requested up front; with two, the MFMA work
+  // per LDS byte is twice as large and the registers are needed for the accumulators instead)
   const char* vbytes = reinterpret_cast<const char*>(vs);
+  constexpr int kHoistV = R == 1 ? 8 : 4;  // dim tiles whose V operands are read before the softmax
   bf16x4 va[8][2];
-#pragma unroll
-  for (int dt = 0; dt < 8; dt++) {
+  auto read_v = [&](int dt) {
 #pragma unroll
     for (int t = 0; t < 2; t++) {
       const int row = 16 * t + 4 * kg + (c >> 2);
@@ -162,7 +164,9 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
       const char* addr = vbytes + row * 256 + slot * 16 + (c & 1) * 8;
       va[dt][t] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(addr));
     }
-  }
+  };
+#pragma unroll
+  for (int dt = 0; dt < kHoistV; dt++) read_v(dt);
   floatx4 s[NV][2];
 #pragma unroll
   for (int rr = 0; rr < NV; rr++) {
@@ -234,6 +238,7 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
     st.lacc[rr] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[rr], st.lacc[rr], 0, 0, 0);
 #pragma unroll
   for (int dt = 0; dt < 8; dt++) {
+    if (dt + 4 < 8 && dt + 4 >= kHoistV) read_v(dt + 4);  // keep four dim tiles of V ahead of the MFMAs
     const bf16x8 a = __builtin_shufflevector(va[dt][0], va[dt][1], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
     for (int rr = 0; rr < NV; rr++)
@@ -247,7 +252,7 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
 __device__ __forceinline__ void pin_args(AttnParams& p) {
   CB_PIN(p.q); CB_PIN(p.out); CB_PIN(p.kv.k); CB_PIN(p.kv.v); CB_PIN(p.kv.block_table);
   CB_PIN(p.kv.seq_stride); CB_PIN(p.kv.token_stride); CB_PIN(p.kv.head_stride); CB_PIN(p.kv.num_blocks);
-  CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.anc); CB_PIN(p.partial); CB_PIN(p.tickets);
+  CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.parent); CB_PIN(p.partial); CB_PIN(p.tickets);
   CB_PIN(p.Hq); CB_PIN(p.Hkv); CB_PIN(p.chunk); CB_PIN(p.nsplit); CB_PIN(p.batch); CB_PIN(p.scale);
   CB_PIN(p.external_merge); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags);
   CB_PIN(p.status); CB_PIN(p.dbg_ts);
@@ -351,14 +356,14 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   const CB_GLOBAL char* kbase = (const CB_GLOBAL char*)p.kv.k;
   const CB_GLOBAL char* vbase = (const CB_GLOBAL char*)p.kv.v;
   const CB_GLOBAL int32_t* gbt = (const CB_GLOBAL int32_t*)p.kv.block_table;
-  const CB_GLOBAL uint32_t* ganc = (const CB_GLOBAL uint32_t*)p.anc;
+  const CB_GLOBAL int32_t* gparent = (const CB_GLOBAL int32_t*)p.parent;
   constexpr int NT = 256 * G;
   constexpr int SK = kStageKeys * G;  // keys per stage
   constexpr int SV = kStageVecs * G;  // 16-byte pieces of K (or V) per stage
   __shared__ uint4 K0[SV], K1[SV], K2[SV], K3[SV];  // one object per ring slot: the compiler tracks
   __shared__ uint4 V0[SV], V1[SV], V2[SV], V3[SV];  // LDS-DMA completion per object
   __shared__ int bt_lds[kMaxBtLds];
-  __shared__ uint32_t anc_lds[RT * kAncWords];
+  __shared__ AncScratch anc_sh;  // ancestor sets of the whole tree, built here by the splits that reach the tree
   __shared__ int last_flag;
   constexpr int D = 128;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
@@ -416,7 +421,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   // Everything this workgroup needs from memory is requested up front, oldest first: the query rows
   // and ancestor words (to registers), then NS-1 stages of K/V (to LDS).
   WaveState<R> st;
-  int row_local[R];   // row index inside the workgroup's tile (for anc_lds)
+  int row_node[R];    // tree node of the lane's query (indexes the ancestor sets)
   int64_t grow[R];    // global output row (node * Hq + head), or -1 past the end
   int nvt = 0;        // this wave's row tiles that hold at least one real row (they come first)
 #pragma unroll
@@ -427,7 +432,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     const bool valid = row < M;
     row = valid ? row : M - 1;
     const int node = row / g, hg = row - node * g;
-    row_local[rr] = valid ? rl : (M - 1 - row0);
+    row_node[rr] = node;
     const int64_t gr = (int64_t)(off + node) * p.Hq + hk * g + hg;
     grow[rr] = valid ? gr : -1;
     const CB_GLOBAL uintx4* qp = (const CB_GLOBAL uintx4*)(gq + gr * D);
@@ -439,15 +444,12 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     st.mref[rr] = -INFINITY;
   }
   const bool tree_split = k1 > S;  // this split reaches the tree nodes: masks needed
-  constexpr int kAncPerThread = (RT * kAncWords + NT - 1) / NT;
-  uint32_t ancv[kAncPerThread];
-  if (tree_split) {
-#pragma unroll
-    for (int i = 0; i < kAncPerThread; i++) {
-      const int idx = tid + i * NT;
-      int row = row0 + idx / kAncWords;
-      row = row < M ? row : M - 1;
-      ancv[i] = (idx < RT * kAncWords) ? ganc[(int64_t)(off + row / g) * kAncWords + (idx % kAncWords)] : 0u;
+  // the tree itself: one parent entry per thread, requested before the K/V loads
+  int my_parent = -1;
+  if (tree_split && tid < N && tid < CB_MAX_NODES) {
+    if (tid > 0) {
+      my_parent = gparent[off + tid];
+      if (my_parent < 0 || my_parent >= tid) my_parent = 0;  // (same repair as the acceptance kernel, which reports it)
     }
   }
 
@@ -465,20 +467,13 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     if (2 < nst) CB_ISSUE(2, 2);
   }
   CB_TS(2);
-  if (tree_split) {
-#pragma unroll
-    for (int i = 0; i < kAncPerThread; i++) {
-      const int idx = tid + i * NT;
-      if (idx < RT * kAncWords) anc_lds[idx] = ancv[i];
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // written before the first ring barrier below
-  }
+  if (tree_split) build_ancestor_sets(anc_sh, N, my_parent);  // uniform in the workgroup; hidden behind the first K/V wait
 
 // the row tiles of a wave that lie past the sequence's rows are left out (R = 2: all, one or none)
 #define CB_COMPUTE(kp, vp, key0, need_mask)                                                                    \
   do {                                                                                                         \
-    if (nvt == R) compute_stage<R, R>(kp, vp, st, c2, key0, S, k1, need_mask, anc_lds, row_local, l);          \
-    else if (R > 1) compute_stage<R, 1>(kp, vp, st, c2, key0, S, k1, need_mask, anc_lds, row_local, l);        \
+    if (nvt == R) compute_stage<R, R>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);  \
+    else if (R > 1) compute_stage<R, 1>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);\
   } while (0)
 #define CB_STAGE(J, JPREV)                                                                         \
   {                                                                                                \

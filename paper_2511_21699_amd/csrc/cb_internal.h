@@ -70,11 +70,79 @@ __device__ __forceinline__ int64_t slot_offset(const KvAddr& a, int seq, int slo
   return (int64_t)seq * a.seq_stride + (int64_t)slot * a.token_stride + (int64_t)head * a.head_stride;
 }
 
+// Ancestor sets of one tree built inside a workgroup (any block size >= 256; the first 256 threads
+// own one node each).  Section 3.2 of the paper: a tree token attends only to its ancestors (and, in
+// this library's reading, itself); anc[i] is the 256-bit set {i, parent(i), parent(parent(i)), ...}.
+// Pointer jumping: after r rounds a node knows its 2^r nearest ancestors, so eight rounds cover any
+// tree of up to 256 nodes whatever its depth.  `parent_of` is the node's sanitised parent (-1 at the
+// root) for threads < N.  On return anc_out[i][0..7] holds node i's set for every i < N and all
+// threads have passed a barrier.  The barriers are bare s_barrier instructions (LDS traffic is
+// ordered by explicit lgkmcnt waits), so the routine can run while global->LDS loads are in flight.
+struct AncScratch {
+  uint32_t anc[CB_MAX_NODES][kAncWords];
+  int jump[CB_MAX_NODES];
+};
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ void build_ancestor_sets(AncScratch& sh, int N, int parent_of) {
+  const int t = threadIdx.x;
+  uint32_t mine[kAncWords];
+  int j = -1;
+  if (t < CB_MAX_NODES) {
+#pragma unroll
+    for (int w = 0; w < kAncWords; w++) mine[w] = (t < N && (t >> 5) == w) ? (1u << (t & 31)) : 0u;
+    j = t < N ? parent_of : -1;
+#pragma unroll
+    for (int w = 0; w < kAncWords; w++) sh.anc[t][w] = mine[w];
+    sh.jump[t] = j;
+  }
+  for (int r = 0; r < 8; r++) {
+    lds_barrier();
+    uint32_t other[kAncWords];
+    int jj = -1;
+    if (t < CB_MAX_NODES && j >= 0) {
+#pragma unroll
+      for (int w = 0; w < kAncWords; w++) other[w] = sh.anc[j][w];
+      jj = sh.jump[j];
+    }
+    lds_barrier();
+    if (t < CB_MAX_NODES && j >= 0) {
+#pragma unroll
+      for (int w = 0; w < kAncWords; w++) {
+        mine[w] |= other[w];
+        sh.anc[t][w] = mine[w];
+      }
+      j = jj;
+      sh.jump[t] = j;
+    }
+  }
+  lds_barrier();
+}
+
+// Parent of node t of a tree as the kernels use it: -1 at the root, entries outside [0, t) become
+// 0 ("child of the root"), and the status word gets bit 0 when an entry had to be repaired.
+__device__ __forceinline__ int sanitized_parent(const int32_t* parent, int off, int t, int32_t* status) {
+  if (t == 0) {
+    if (parent[off] != -1 && status) atomicOr(status, 1);
+    return -1;
+  }
+  int p = parent[off + t];
+  if (p < 0 || p >= t) {
+    if (status) atomicOr(status, 1);
+    p = 0;
+  }
+  return p;
+}
+
 struct AttnParams {
   const void* q;     // [sumN][Hq][D]
   void* out;         // [sumN][Hq][D]
   KvAddr kv;
-  const uint32_t* anc;  // [sumN][kAncWords]
+  const uint32_t* anc;  // [sumN][kAncWords] (scalar kernel; the MFMA kernel builds the sets itself)
+  const int32_t* parent;  // [sumN] device tree, local parent indices
   float* partial;       // [sumN*Hq][nsplit][partial_stride(D)]: o[D] (unnormalised), m, l, pad
   uint32_t* tickets;    // one counter per (sequence, kv head, row tile)
   int32_t Hq, Hkv, D;
@@ -103,7 +171,7 @@ hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows
                          ArgmaxPartial* partial, int nchunks, int batch, const SeqMeta& meta,
                          const int32_t* prep_parent, int max_depth, uint32_t* prep_anc, int32_t* status);
 hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
-                         const int32_t* tokens, const uint32_t* anc, const ArgmaxPartial* partial,
+                         const int32_t* tokens, int32_t* status, const ArgmaxPartial* partial,
                          int nchunks, int max_depth, int32_t* argmax_out, int32_t* path,
                          int32_t* len_ctx, int32_t* len_user, int32_t* tok_user);
 hipError_t launch_compact(hipStream_t st, int batch, const SeqMeta& meta, const KvAddr* layers,

@@ -10,19 +10,6 @@ namespace cb {
 // Built by pointer jumping in LDS: after r rounds a node knows its 2^r nearest ancestors, so eight
 // rounds cover any tree of up to 256 nodes whatever its depth.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ int sanitized_parent(const int32_t* parent, int off, int t, int32_t* status) {
-  if (t == 0) {
-    if (parent[off] != -1 && status) atomicOr(status, 1);
-    return -1;
-  }
-  int p = parent[off + t];
-  if (p < 0 || p >= t) {
-    if (status) atomicOr(status, 1);
-    p = 0;
-  }
-  return p;
-}
-
 struct PrepareLds {
   uint32_t A[2][CB_MAX_NODES][kAncWords];
   int J[2][CB_MAX_NODES];
@@ -196,12 +183,13 @@ hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_accept(SeqMeta meta, const int32_t* __restrict__ parent,
                                                 const int32_t* __restrict__ tokens,
-                                                const uint32_t* __restrict__ anc,
+                                                int32_t* status,
                                                 const ArgmaxPartial* __restrict__ partial, int nchunks,
                                                 int max_depth, int32_t* __restrict__ argmax_out,
                                                 int32_t* __restrict__ path, int32_t* len_ctx,
                                                 int32_t* len_user, int32_t* __restrict__ tok_user) {
   __shared__ int sh_a[CB_MAX_NODES];
+  __shared__ AncScratch sh_anc;
   __shared__ uint32_t sh_match[kAncWords];
   __shared__ uint32_t sh_best[kAncWords];
   __shared__ uint32_t sh_key[4];
@@ -223,10 +211,12 @@ __global__ __launch_bounds__(256) void k_accept(SeqMeta meta, const int32_t* __r
   sh_a[t] = a;
   __syncthreads();
   bool match = false;
+  int par = -1;
   if (t < N) {
-    int p = sanitized_parent(parent, off, t, nullptr);
-    match = (t == 0) || (tokens[off + t] == sh_a[p]);
+    par = sanitized_parent(parent, off, t, status);
+    match = (t == 0) || (tokens[off + t] == sh_a[par]);
   }
+  build_ancestor_sets(sh_anc, N, par);  // (the attention kernels build their own; nothing is passed between them)
   const unsigned long long bal = __ballot(match);
   if ((t & 63) == 0) {
     sh_match[(t >> 6) * 2] = (uint32_t)bal;
@@ -238,11 +228,14 @@ __global__ __launch_bounds__(256) void k_accept(SeqMeta meta, const int32_t* __r
   bool acc = t < N;
 #pragma unroll
   for (int w = 0; w < kAncWords; w++) {
-    my[w] = (t < N) ? anc[(int64_t)(off + t) * kAncWords + w] : 0u;
+    my[w] = (t < N) ? sh_anc.anc[t][w] : 0u;
     depth += __popc(my[w]);
     acc = acc && ((my[w] & ~sh_match[w]) == 0u);
   }
-  if (depth > max_depth) acc = false;
+  if (depth > max_depth) {
+    acc = false;
+    if (t < N) atomicOr(status, 2);
+  }
   uint32_t key = acc ? ((uint32_t)(depth + 1) << 16) | (uint32_t)(0xffff - t) : 0u;
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) {
@@ -276,10 +269,10 @@ __global__ __launch_bounds__(256) void k_accept(SeqMeta meta, const int32_t* __r
 }
 
 hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
-                         const int32_t* tokens, const uint32_t* anc, const ArgmaxPartial* partial,
+                         const int32_t* tokens, int32_t* status, const ArgmaxPartial* partial,
                          int nchunks, int max_depth, int32_t* argmax_out, int32_t* path,
                          int32_t* len_ctx, int32_t* len_user, int32_t* tok_user) {
-  hipLaunchKernelGGL(k_accept, dim3(batch), dim3(256), 0, st, meta, parent, tokens, anc, partial, nchunks,
+  hipLaunchKernelGGL(k_accept, dim3(batch), dim3(256), 0, st, meta, parent, tokens, status, partial, nchunks,
                      max_depth, argmax_out, path, len_ctx, len_user, tok_user);
   return hipGetLastError();
 }
