@@ -102,6 +102,17 @@ int cb_workspace_bytes(const cb_config *cfg, size_t *bytes);
  * Clears the workspace's counters on the default (null) stream and waits for that. */
 int cb_init(const cb_config *cfg, void *workspace, size_t workspace_bytes, cb_ctx **out);
 
+/* Host-only: how the attention stage (Section 3.2, tree attention over prefix + ancestors) would be
+ * cut up for these lengths, without touching a device.  plan[0] = kernel family (1 scalar, 2 MFMA),
+ * plan[1] = partial slots per output row (splits of the longest sequence), plan[2] = keys per split
+ * (a multiple of 32; splits x keys covers the longest sequence, shorter sequences use fewer splits),
+ * plan[3] = output rows per workgroup tile (1 for the scalar family), plan[4] = workgroups launched
+ * that have keys to sweep.  forced_splits > 0 overrides the planner's split count (capped at the
+ * configuration's max_splits), like the "splits" option.  All arrays are host memory.  CB_EINVAL on
+ * a bad configuration or shape. */
+int cb_plan_attention(const cb_config *cfg, int32_t batch, const int32_t *kv_len,
+                      const int32_t *node_offsets, int32_t forced_splits, int32_t plan[5]);
+
 /* Host-only argument check used by cb_verify_tree (exported so it can be exercised without a GPU):
  * shapes against the configuration, tree well-formedness, cache capacity.  `err`/`err_len` may be
  * NULL/0; otherwise a text is written on failure. */

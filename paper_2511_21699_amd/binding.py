@@ -20,7 +20,7 @@ CB_OK, CB_EINVAL, CB_ETREE, CB_ECAP, CB_ESTATE, CB_EHIP = range(6)
 CB_LAYOUT_TOKEN_MAJOR, CB_LAYOUT_HEAD_MAJOR = 0, 1
 ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_ESTATE", 5: "CB_EHIP"}
 
-EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_verify_tree", "cb_verify_tree_device",
+EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device",
            "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
            "cb_last_attention_ms", "cb_debug_timestamps", "cb_last_error", "cb_destroy"]
 
@@ -59,6 +59,7 @@ def load():
     L.cb_init.argtypes = [C.POINTER(CbConfig), vp, C.c_size_t, C.POINTER(vp)]
     L.cb_check_verify_args.argtypes = [C.POINTER(CbConfig), C.c_int32, C.POINTER(CbKvLayer), i32p, i32p, i32p,
                                        C.c_char_p, C.c_size_t]
+    L.cb_plan_attention.argtypes = [C.POINTER(CbConfig), C.c_int32, i32p, i32p, C.c_int32, i32p]
     L.cb_verify_tree.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, i32p, i32p, vp, vp, i32p, i32p]
     L.cb_verify_tree_device.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, vp, vp, vp, vp, vp, vp]
     L.cb_compact_kv.argtypes = [vp, vp, C.c_int32, C.POINTER(CbKvLayer), i32p]
@@ -111,6 +112,16 @@ def check_verify_args(cfg: CbConfig, batch: int, kv: CbKvLayer, kv_len, node_off
     a, b, c = _i32(kv_len), _i32(node_offsets), _i32(parent)
     rc = L.cb_check_verify_args(C.byref(cfg), batch, C.byref(kv), _ip(a), _ip(b), _ip(c), buf, 256)
     return rc, buf.value.decode()
+
+
+def plan_attention(cfg: CbConfig, kv_len, node_offsets, forced_splits: int = 0) -> dict:
+    """Host-only: the attention stage's split plan for these lengths (no GPU needed)."""
+    a, b = _i32(kv_len), _i32(node_offsets)
+    out = (C.c_int32 * 5)()
+    rc = load().cb_plan_attention(C.byref(cfg), len(a), _ip(a), _ip(b), forced_splits, out)
+    if rc:
+        raise CbError(rc, "cb_plan_attention rejected the shape")
+    return dict(impl=out[0], nsplit=out[1], chunk=out[2], tile_rows=out[3], workgroups=out[4])
 
 
 def workspace_bytes(cfg: CbConfig) -> int:

@@ -159,8 +159,9 @@ struct Plan {
   int max_nodes, max_len;
 };
 
-Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const int32_t* node_offsets) {
-  const cb_config& c = ctx->cfg;
+// Pure host arithmetic: no device call, no context state beyond the three numbers passed in.
+Plan plan_attention(const cb_config& c, int max_splits, int opt_impl, int opt_splits, int batch,
+                    const int32_t* kv_len, const int32_t* node_offsets) {
   Plan p{};
   int64_t rows = 0;
   for (int b = 0; b < batch; b++) {
@@ -170,11 +171,10 @@ Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const i
     rows += (int64_t)n * c.num_q_heads;
   }
   const bool mfma_ok = c.qkv_dtype == CB_BF16 && c.head_dim == 128;
-  p.impl = ctx->opt_impl == 1 ? 1 : (ctx->opt_impl == 2 ? (mfma_ok ? 2 : 1) : (mfma_ok ? 2 : 1));
-  const int max_splits = ctx->lay.max_splits;
+  p.impl = (opt_impl == 1 || !mfma_ok) ? 1 : 2;
   int nsplit;
-  if (ctx->opt_splits > 0) {
-    nsplit = (int)std::min<int64_t>(ctx->opt_splits, max_splits);
+  if (opt_splits > 0) {
+    nsplit = (int)std::min<int64_t>(opt_splits, max_splits);
   } else if (p.impl == 1) {
     // one workgroup per (row, split): aim for a few workgroups per compute unit, but never split
     // below 1024 keys -- a second (merge) launch costs more than a short row does
@@ -185,9 +185,6 @@ Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const i
     const int g = c.num_q_heads / c.num_kv_heads;
     const int mrows = p.max_nodes * g;
     const int rows_per_wg = attn_mfma_tile_rows(mrows);
-    int64_t tiles = 0;
-    for (int b = 0; b < batch; b++)
-      tiles += (int64_t)(((node_offsets[b + 1] - node_offsets[b]) * g + rows_per_wg - 1) / rows_per_wg) * c.num_kv_heads;
     // Every variant runs 8 waves and a 128 KiB ring: one workgroup per compute unit, so the grid
     // should come out just under a whole number of rounds of 256 workgroups.  Take the fewest
     // splits that fill >= 85% of the machine in whole rounds (fewer splits = fewer partials).
@@ -212,7 +209,6 @@ Plan plan_attention(const cb_ctx* ctx, int batch, const int32_t* kv_len, const i
       if (eff >= 0.85) { nsplit = ns; best = eff; break; }
       if (eff > best) { best = eff; nsplit = ns; }
     }
-    (void)tiles;
   }
   nsplit = std::max(1, std::min(nsplit, max_splits));
   int chunk = (p.max_len + nsplit - 1) / nsplit;
@@ -242,7 +238,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   for (int b = 0; b < batch; b++) meta.kv_len[b] = kv_len[b];
   for (int b = 0; b <= batch; b++) meta.node_off[b] = node_offsets[b];
   const int total = node_offsets[batch];
-  const Plan plan = plan_attention(ctx, batch, kv_len, node_offsets);
+  const Plan plan = plan_attention(c, ctx->lay.max_splits, ctx->opt_impl, ctx->opt_splits, batch, kv_len, node_offsets);
 
   AttnParams ap{};
   ap.q = q;
@@ -325,6 +321,31 @@ int cb_workspace_bytes(const cb_config* cfg, size_t* bytes) {
   if (!bytes) return set_err(nullptr, CB_EINVAL, "null bytes");
   if (!config_ok(cfg, g_init_err, sizeof g_init_err)) return CB_EINVAL;
   *bytes = ws_layout(*cfg).total;
+  return CB_OK;
+}
+
+int cb_plan_attention(const cb_config* cfg, int32_t batch, const int32_t* kv_len, const int32_t* node_offsets,
+                      int32_t forced_splits, int32_t plan[5]) {
+  if (!config_ok(cfg, nullptr, 0) || !kv_len || !node_offsets || !plan) return CB_EINVAL;
+  if (batch < 1 || batch > cfg->max_batch || node_offsets[0] != 0) return CB_EINVAL;
+  for (int b = 0; b < batch; b++) {
+    const int64_t n = (int64_t)node_offsets[b + 1] - node_offsets[b];
+    if (n < 1 || n > cfg->max_nodes || kv_len[b] < 0 || (int64_t)kv_len[b] + n > (1ll << 30)) return CB_EINVAL;
+  }
+  const Plan p = plan_attention(*cfg, effective_max_splits(*cfg), 0, forced_splits, batch, kv_len, node_offsets);
+  const int g = cfg->num_q_heads / cfg->num_kv_heads;
+  const int tile = p.impl == 2 ? attn_mfma_tile_rows(p.max_nodes * g) : 1;
+  int64_t wgs = 0;
+  for (int b = 0; b < batch; b++) {
+    const int n = node_offsets[b + 1] - node_offsets[b];
+    const int64_t units = p.impl == 2 ? (int64_t)((n * g + tile - 1) / tile) * cfg->num_kv_heads : (int64_t)n * cfg->num_q_heads;
+    wgs += units * ((kv_len[b] + n + p.chunk - 1) / p.chunk);
+  }
+  plan[0] = p.impl;
+  plan[1] = p.nsplit;
+  plan[2] = p.chunk;
+  plan[3] = tile;
+  plan[4] = (int32_t)std::min<int64_t>(wgs, INT32_MAX);
   return CB_OK;
 }
 

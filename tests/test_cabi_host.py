@@ -79,3 +79,61 @@ def test_init_without_device_fails_cleanly():
     ctx = C.c_void_p()
     rc = lib.cb_init(C.byref(cfg), 0x10000, 1 << 30, C.byref(ctx))
     assert rc == B.CB_EHIP and not ctx.value and lib.cb_last_error(None)
+
+
+def _plan_invariants(cfg, kv_len, offs, plan, g):
+    n = np.diff(offs)
+    lens = np.asarray(kv_len) + n
+    assert plan["chunk"] % 32 == 0 and plan["chunk"] >= 32
+    assert plan["nsplit"] >= 1
+    cap = cfg.max_splits if cfg.max_splits > 0 else 64
+    assert plan["nsplit"] <= cap
+    # the splits cover the longest sequence exactly once, with no empty trailing split
+    assert plan["nsplit"] * plan["chunk"] >= lens.max()
+    assert (plan["nsplit"] - 1) * plan["chunk"] < lens.max()
+    if plan["impl"] == 2:
+        assert plan["tile_rows"] in (64, 128, 256)
+        assert plan["tile_rows"] >= min(256, n.max() * g) or plan["tile_rows"] == 256
+        tiles = -(-(n * g) // plan["tile_rows"]) * cfg.num_kv_heads
+    else:
+        assert plan["tile_rows"] == 1
+        tiles = n * cfg.num_q_heads
+    assert plan["workgroups"] == int((tiles * -(-lens // plan["chunk"])).sum())
+
+
+def test_attention_plan_invariants_on_the_paper_shapes_and_random_batches():
+    # the five workload shapes: (Hq, Hkv, D, dtype, kv_len, node counts, block)
+    shapes = [(8, 8, 64, "f32", [256], [15], 0), (32, 32, 128, "bf16", [2048], [64], 0),
+              (32, 8, 128, "bf16", [8192], [128], 0), (40, 40, 128, "bf16", [65536], [256], 0)]
+    for Hq, Hkv, D, dt, kv, n, blk in shapes:
+        cfg = B.make_config(Hq, Hkv, D, dt, dt, len(kv), max(n), 8, 1000, blk)
+        offs = np.concatenate([[0], np.cumsum(n)])
+        plan = B.plan_attention(cfg, kv, offs)
+        _plan_invariants(cfg, kv, offs, plan, Hq // Hkv)
+        assert plan["impl"] == (2 if (dt == "bf16" and D == 128) else 1)
+    # the 7B-shaped step fills the chip's 256 compute units in one round
+    cfg = B.make_config(32, 32, 128, "bf16", "bf16", 1, 64, 8, 32000)
+    plan = B.plan_attention(cfg, [2048], [0, 64])
+    assert 218 <= plan["workgroups"] <= 256 and plan["tile_rows"] == 64
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        Bn = int(rng.integers(1, 17))
+        Hkv = int(rng.choice([1, 2, 8, 32]))
+        g = int(rng.choice([1, 4, 8]))
+        n = rng.integers(1, 97, Bn)
+        kv = rng.integers(0, 20000, Bn)
+        ms = int(rng.choice([0, 1, 3, 16, 200]))
+        cfg = B.make_config(Hkv * g, Hkv, 128, "bf16", "bf16", Bn, 96, 8, 1000, 16, ms)
+        offs = np.concatenate([[0], np.cumsum(n)])
+        _plan_invariants(cfg, kv, offs, B.plan_attention(cfg, kv, offs), g)
+        forced = int(rng.integers(1, 40))
+        p = B.plan_attention(cfg, kv, offs, forced)
+        _plan_invariants(cfg, kv, offs, p, g)
+        assert p["nsplit"] <= forced
+
+
+def test_attention_plan_rejects_bad_shapes():
+    cfg = B.make_config(8, 8, 128, "bf16", "bf16", 2, 8, 3, 100)
+    for kv, offs in (([5], [1, 4]), ([5], [0, 0]), ([5], [0, 9]), ([-1], [0, 3]), ([1, 2, 3], [0, 1, 2, 3])):
+        with pytest.raises(B.CbError):
+            B.plan_attention(cfg, kv, offs)
