@@ -7,7 +7,7 @@
 #include <algorithm>
 #include <new>
 
-#include "cb_internal.h"
+#include "cb_logits.h"
 
 using namespace cb;
 
@@ -20,7 +20,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
   size_t anc, parent, tokens, amax_partial, amax_out, path, len_ctx, res_len, res_tok, new_len, status,
-      tickets, dbg, partial, total;
+      tickets, amax_tickets, amax_lines, dbg, partial, total;
   int amax_chunks;
   int max_total_nodes;
   int max_splits;
@@ -73,6 +73,9 @@ WsLayout ws_layout(const cb_config& c) {
   L.new_len = take(c.max_batch * 4);
   L.status = take(4);
   L.tickets = take((size_t)L.ticket_count * 4);
+  L.amax_tickets = take(CB_MAX_BATCH * 4);
+  // argmax partials of the one-launch verification, one 128-byte line each (it takes sequences of at most 64 nodes)
+  L.amax_lines = take((size_t)c.max_batch * std::min(c.max_nodes, 64) * L.amax_chunks * 128);
   L.dbg = take(1024 * 8 * 8);
   L.partial = take(mt * c.num_q_heads * (size_t)L.max_splits * partial_stride(c.head_dim) * 4);
   L.total = o;
@@ -103,7 +106,7 @@ struct cb_ctx {
   int32_t last_len[CB_MAX_BATCH];
   hipStream_t last_stream;
   // options
-  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug, opt_fork;
+  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug, opt_fork, opt_fuse;
   hipEvent_t ev0, ev1, ev_fork, ev_join;
   hipStream_t aux;  // second stream (default priority) for the logits scan beside the attention
   bool ev_valid;
@@ -258,6 +261,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.status = ctx->dev<int32_t>(ctx->lay.status);
   ap.dbg_ts = ctx->dev<unsigned long long>(ctx->lay.dbg);
   ap.debug_flags = (int32_t)ctx->opt_debug;
+  ap.max_depth = c.max_depth;
 
   const int64_t stages = ctx->opt_stages;  // measurement aid: bit 0 ancestor sets, 1 attention, 2 argmax, 3 acceptance
   const bool use_mfma = plan.impl == 2 && attn_mfma_supports(ap);
@@ -267,14 +271,33 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   // on the 7B shape the cross-stream edges cost more than the 5 us scan they hide, so it is off by
   // default.  The scalar attention reads the sets from the workspace: there the scan goes first and
   // carries the blocks that build them.
-  const bool fork = ctx->opt_fork != 0 && use_mfma && (stages & 2) && (stages & 4);
+  AcceptArgs acc{};
+  acc.parent = d_parent;
+  acc.tokens = d_tokens;
+  acc.status = ctx->dev<int32_t>(ctx->lay.status);
+  acc.partial = ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial);
+  acc.slot_stride = 1;
+  acc.nchunks = ctx->lay.amax_chunks;
+  acc.max_depth = c.max_depth;
+  acc.argmax_out = ctx->dev<int32_t>(ctx->lay.amax_out);
+  acc.path = ctx->dev<int32_t>(ctx->lay.path);
+  acc.len_ctx = ctx->dev<int32_t>(ctx->lay.len_ctx);
+  acc.len_user = d_len;
+  acc.tok_user = d_tok;
+  // Small calls with the MFMA attention are one launch: the attention workgroups also scan the
+  // logits and run the acceptance (option "fuse_logits", on by default; see attn_mfma_can_fuse).
+  // Otherwise the scan, the attention and the acceptance are launches of their own.
+  const bool fused = use_mfma && ctx->opt_fuse != 0 && (stages & 2) && (stages & 4) && (stages & 8) &&
+                     attn_mfma_can_fuse(ap, plan.max_nodes, (int64_t)total * ctx->lay.amax_chunks, c.logits_dtype);
+  const bool fork = !fused && ctx->opt_fork != 0 && use_mfma && (stages & 2) && (stages & 4);
   hipStream_t scan_stream = st;
   if (fork) {
     CB_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
     CB_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0));
     scan_stream = ctx->aux;
   }
-  if (stages & 4) {
+  if (fused) {
+  } else if (stages & 4) {
     const bool carry = !use_mfma && (stages & 1);
     CB_HIP(ctx, launch_argmax(scan_stream, logits, c.logits_dtype, total, c.vocab_size,
                               ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
@@ -289,7 +312,17 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   if (timing) CB_HIP(ctx, hipEventRecord(ctx->ev0, st));
   if (!(stages & 2)) {
   } else if (use_mfma) {
-    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total));  // merges its own splits
+    LogitsWork lw{};
+    lw.logits = static_cast<const uint16_t*>(logits);
+    lw.V = c.vocab_size;
+    lw.rows = total;
+    lw.batch = batch;
+    lw.tickets = ctx->dev<uint32_t>(ctx->lay.amax_tickets);
+    lw.accept = acc;
+    lw.accept.partial = ctx->dev<ArgmaxPartial>(ctx->lay.amax_lines);
+    lw.accept.slot_stride = 16;
+    lw.partial_out = ctx->dev<ArgmaxPartial>(ctx->lay.amax_lines);
+    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total, fused ? &lw : nullptr));  // merges its own splits
   } else {
     CB_HIP(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
     if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
@@ -299,11 +332,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
     ctx->ev_valid = true;
   }
   if (fork) CB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
-  if (stages & 8)
-    CB_HIP(ctx, launch_accept(st, batch, meta, d_parent, d_tokens, ctx->dev<int32_t>(ctx->lay.status),
-                              ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, c.max_depth,
-                              ctx->dev<int32_t>(ctx->lay.amax_out), ctx->dev<int32_t>(ctx->lay.path),
-                              ctx->dev<int32_t>(ctx->lay.len_ctx), d_len, d_tok));
+  if ((stages & 8) && !fused) CB_HIP(ctx, launch_accept(st, batch, meta, acc));
   ctx->meta = meta;
   ctx->batch = batch;
   ctx->total_nodes = total;
@@ -409,6 +438,7 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   ctx->lay = lay;
   ctx->ws = static_cast<char*>(workspace);
   ctx->opt_stages = 15;
+  ctx->opt_fuse = 1;
   const size_t mt = lay.max_total_nodes, stride = (size_t)cfg->max_depth + 1;
   const size_t ints = mt * 3 + cfg->max_batch * (1 + 2 * stride) + 1 + cfg->max_batch;
   hipError_t e = hipHostMalloc(&ctx->h_block, ints * 4, hipHostMallocDefault);
@@ -431,6 +461,7 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipMemset(ctx->ws + lay.status, 0, 4);
   if (e == hipSuccess) e = hipMemset(ctx->ws + lay.tickets, 0, (size_t)lay.ticket_count * 4);
+  if (e == hipSuccess) e = hipMemset(ctx->ws + lay.amax_tickets, 0, CB_MAX_BATCH * 4);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     (void)hipHostFree(ctx->h_block);
@@ -577,6 +608,7 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   else if (!strcmp(name, "stages")) ctx->opt_stages = value & 15;
   else if (!strcmp(name, "debug_flags")) ctx->opt_debug = value;
   else if (!strcmp(name, "parallel_scan")) ctx->opt_fork = value;
+  else if (!strcmp(name, "fuse_logits")) ctx->opt_fuse = value;
   else return set_err(ctx, CB_EINVAL, "unknown option '%s'", name);
   return CB_OK;
 }

@@ -21,7 +21,7 @@
 //   16(e/4)+4kg+e%4), A = V^T must hold the same keys for dim c of the 16-dim tile; it is fetched
 //   from the row-major V tile with ds_read_b64_tr_b16 (each 16-lane group reads a 4-key x 16-dim
 //   block and receives it transposed).  D[v] = O^T[dim 4kg+v][query c].
-#include "cb_internal.h"
+#include "cb_logits.h"
 
 namespace cb {
 
@@ -254,8 +254,22 @@ __device__ __forceinline__ void pin_args(AttnParams& p) {
   CB_PIN(p.kv.seq_stride); CB_PIN(p.kv.token_stride); CB_PIN(p.kv.head_stride); CB_PIN(p.kv.num_blocks);
   CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.parent); CB_PIN(p.partial); CB_PIN(p.tickets);
   CB_PIN(p.Hq); CB_PIN(p.Hkv); CB_PIN(p.chunk); CB_PIN(p.nsplit); CB_PIN(p.batch); CB_PIN(p.scale);
-  CB_PIN(p.external_merge); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags);
+  CB_PIN(p.external_merge); CB_PIN(p.max_depth); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags);
   CB_PIN(p.status); CB_PIN(p.dbg_ts);
+}
+__device__ __forceinline__ void pin_logits_args(LogitsWork& w) {
+  CB_PIN(w.logits); CB_PIN(w.V); CB_PIN(w.rows); CB_PIN(w.batch); CB_PIN(w.partial_out);
+  CB_PIN(w.tickets); CB_PIN(w.accept.parent); CB_PIN(w.accept.tokens); CB_PIN(w.accept.status);
+  CB_PIN(w.accept.partial); CB_PIN(w.accept.slot_stride); CB_PIN(w.accept.nchunks); CB_PIN(w.accept.max_depth);
+  CB_PIN(w.accept.argmax_out); CB_PIN(w.accept.path); CB_PIN(w.accept.len_ctx); CB_PIN(w.accept.len_user);
+  CB_PIN(w.accept.tok_user);
+  // (the pinned pointers have lost their address space: say again that they are global memory)
+#define CB_REGLOBAL(x) x = (decltype(x))(CB_GLOBAL void*)(x)
+  CB_REGLOBAL(w.logits); CB_REGLOBAL(w.partial_out); CB_REGLOBAL(w.tickets); CB_REGLOBAL(w.accept.parent);
+  CB_REGLOBAL(w.accept.tokens); CB_REGLOBAL(w.accept.status); CB_REGLOBAL(w.accept.partial);
+  CB_REGLOBAL(w.accept.argmax_out); CB_REGLOBAL(w.accept.path); CB_REGLOBAL(w.accept.len_ctx);
+  CB_REGLOBAL(w.accept.len_user); CB_REGLOBAL(w.accept.tok_user);
+#undef CB_REGLOBAL
 }
 #undef CB_PIN
 
@@ -339,15 +353,17 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_
 // combined through LDS at the end).  With SEQ = true every wave owns its own 16*R rows -- the tile
 // has 64*R*G rows -- and walks through all G key halves of a stage itself, so K/V is read from HBM
 // once for a tile of up to 256 rows.
-template <int R, int G, bool SEQ>
-__global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta meta) {
+// `hook` (FUSE only) is the workgroup's share of the logits work; with one row tile per wave there
+// are registers to spare and its first item is woven into the tail of the attention (see LogitsHook).
+template <int R, int G, bool SEQ, bool FUSE>
+__device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMetaLanes& ml, unsigned long long ts0,
+                                          LogitsHook<256 * G>* hook) {
+  constexpr bool kHookEarly = FUSE && R == 1;
   static_assert(G == 1 || (G == 2 && R <= 2), "two wave groups are built for one or two row tiles per wave");
   constexpr int RT = 64 * R * (SEQ ? G : 1);  // rows of the workgroup's tile
   // All kernel arguments are fetched in one burst at entry (see pin_args): left to itself the
   // compiler loads each near its first use, behind early exits, and the chain of dependent scalar
   // loads then costs several microseconds before the first K/V request goes out.
-  const unsigned long long ts0 = wall_clock64();
-  const SeqMetaLanes ml = seq_meta_prefetch(meta);
   AttnParams p = p_arg;
   pin_args(p);
   // (the pinned pointers have lost their address space: say again that they are global memory)
@@ -467,7 +483,11 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     if (2 < nst) CB_ISSUE(2, 2);
   }
   CB_TS(2);
-  if (tree_split) build_ancestor_sets(anc_sh, N, my_parent);  // uniform in the workgroup; hidden behind the first K/V wait
+  // The workgroup's logits item is requested behind the K/V prologue, into registers, and used after
+  // the sweep.  The ring's waits count the newest requests a wave may leave in flight (vmcnt <= 8,
+  // 4, 0); these extra loads only make such a wait cover more than it needs to, never less.
+  if constexpr (kHookEarly) hook->prefetch_first();
+  if (tree_split) build_ancestor_sets(anc_sh, N, my_parent, jump_rounds(p.max_depth));  // uniform in the workgroup; hidden behind the first K/V wait
 
 // the row tiles of a wave that lie past the sequence's rows are left out (R = 2: all, one or none)
 #define CB_COMPUTE(kp, vp, key0, need_mask)                                                                    \
@@ -504,6 +524,10 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
 
   CB_TS(4);
   if (p.debug_flags & 8) return;  // (timing aid: stop after the key sweep)
+  if constexpr (kHookEarly) {
+    hook->scan_first();  // its store completes together with the partials' stores below
+    hook->stamp(2);
+  }
 
   if constexpr (G == 2 && !SEQ) {
     // combine the two wave groups' softmax states: group 1 parks (o, mref, l) in the ring, group 0 adds it
@@ -542,6 +566,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     }
   }
 
+  if constexpr (kHookEarly) hook->stamp(3);
   // Buffer descriptor over this sequence's partials (byte offsets fit 32 bits, checked by the launcher).
   const int64_t seq_row0 = (int64_t)off * p.Hq;
   const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -583,6 +608,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
       }
     }
   }
+  if constexpr (kHookEarly) hook->stamp(4);
   if (nsplit_b == 1 || p.external_merge) return;  // (a following kernel merges: the kernel boundary orders the stores)
 
   // ---- split merge by the last workgroup of this (sequence, kv head, row tile) to finish.
@@ -603,6 +629,8 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
     // (hardware register 20, bits 3:0): all ids equal mine  <=>  sum = n*id and sumsq = n*id*id.
     const unsigned long long x = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
     const unsigned long long mine = 1ull | (x << 16) | ((x * x) << 36);
+    uint32_t scan_old = 0;
+    if constexpr (kHookEarly) scan_old = hook->ticket_first_issue();
     const unsigned long long tot = __hip_atomic_fetch_add(ticket, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
     const unsigned long long n = tot & 0xffffull;
     int flag = (n == (unsigned long long)nsplit_b) ? 1 : 0;
@@ -615,9 +643,17 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
       __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
     }
     last_flag = flag;
+    if constexpr (kHookEarly) hook->ticket_first_resolve(scan_old);
   }
   __syncthreads();
   CB_TS(6);
+  // If this workgroup completed the logits scan, its first wave runs the acceptance now, while the
+  // other waves go straight on to the merge below.
+  if constexpr (kHookEarly) {
+    hook->first_counted();
+    hook->accept_first();
+    hook->stamp(5);
+  }
   if (!last_flag) return;
   // Same XCD: the write-through stores left the lines in this L2, plain (cached) loads are coherent
   // with them.  Otherwise read past the L2 with agent-coherent loads.
@@ -626,6 +662,32 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p_arg, SeqMeta
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   CB_TS(7);
 #undef CB_TS
+}
+
+template <int R, int G, bool SEQ>
+__global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p, SeqMeta meta) {
+  const unsigned long long ts0 = wall_clock64();
+  const SeqMetaLanes ml = seq_meta_prefetch(meta);
+  attn_tile<R, G, SEQ, false>(p, ml, ts0, nullptr);
+}
+
+// The whole verification in one launch: every workgroup does its attention duty (a tile's split,
+// perhaps the tile's merge) and takes its share of the logits scan; the workgroup that completes a
+// sequence's scan runs the sequence's acceptance (LogitsHook of cb_logits.h).  The scan does not
+// depend on the attention, so it needs no ordering against it, and its memory round trips ride on
+// those the split merge needs anyway.
+template <int R, int G, bool SEQ>
+__global__ __launch_bounds__(256 * G) void k_verify_mfma(AttnParams p, SeqMeta meta, LogitsWork lw_arg) {
+  const unsigned long long ts0 = wall_clock64();
+  const SeqMetaLanes ml = seq_meta_prefetch(meta);
+  LogitsWork lw = lw_arg;
+  pin_logits_args(lw);  // fetched with the attention's arguments, not later in front of the first use
+  __shared__ TailLds tail;
+  const int wg = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
+  LogitsHook<256 * G> hook(lw, ml, tail, wg);
+  if ((p.debug_flags & 32) && wg < 512) hook.dbg = p.dbg_ts + (int64_t)(wg + 512) * 8;  // (timing aid: second half of the table)
+  attn_tile<R, G, SEQ, true>(p, ml, ts0, &hook);
+  hook.finish();
 }
 
 // Stand-alone merge of the bf16 partials, used when a tile's partials are too many for one
@@ -705,8 +767,21 @@ bool attn_mfma_supports(const AttnParams& p) {
 // (g query heads x N nodes) per kv head.
 int attn_mfma_tile_rows(int mrows) { return mrows <= 64 ? 64 : (mrows <= 128 ? 128 : 256); }
 
+// Whether the launch for this call can also carry the logits work (k_verify_mfma).  That pays when
+// each workgroup gets at most one logits item and has registers to hold it during the key sweep:
+// the variant with one row tile per wave (so every sequence has at most 64 nodes), no more items
+// than workgroups, bf16 logits.  Larger calls run in several rounds of workgroups, where a
+// stand-alone scan at full occupancy is faster.
+bool attn_mfma_can_fuse(const AttnParams& p, int max_nodes_in_call, int64_t logits_items, int logits_dtype) {
+  if (!attn_mfma_supports(p) || (p.debug_flags & (64 | 128)) || logits_dtype != CB_BF16) return false;
+  const int M = max_nodes_in_call * (p.Hq / p.Hkv);
+  if (attn_mfma_tile_rows(M) != 64) return false;
+  const int64_t T = (int64_t)p.nsplit * p.Hkv * p.batch;
+  return logits_items <= T;
+}
+
 hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
-                            int total_nodes) {
+                            int total_nodes, const LogitsWork* logits_work) {
   if (!attn_mfma_supports(p)) return hipErrorInvalidValue;
   const int g = p.Hq / p.Hkv;
   const int M = max_nodes_in_call * g;
@@ -726,9 +801,15 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   // KiB per tile a separate, fully parallel merge kernel is cheaper than the in-kernel merge
   q.external_merge = (p.nsplit > 1 && (int64_t)p.nsplit * rt_rows * kPartialBytes > 320 * 1024) ? 1 : 0;
   if (p.debug_flags & 256) q.external_merge = 1;  // (timing aid)
-  if (rt_rows == 64) hipLaunchKernelGGL((k_attn_mfma<1, 2, false>), grid, dim3(512), 0, st, q, meta);
-  else if (rt_rows == 128) hipLaunchKernelGGL((k_attn_mfma<2, 2, false>), grid, dim3(512), 0, st, q, meta);
-  else hipLaunchKernelGGL((k_attn_mfma<2, 2, true>), grid, dim3(512), 0, st, q, meta);
+  if (logits_work) {
+    const LogitsWork& lw = *logits_work;
+    if (!attn_mfma_can_fuse(p, max_nodes_in_call, (int64_t)lw.rows * lw.accept.nchunks, CB_BF16)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_verify_mfma<1, 2, false>), grid, dim3(512), 0, st, q, meta, lw);
+  } else {
+    if (rt_rows == 64) hipLaunchKernelGGL((k_attn_mfma<1, 2, false>), grid, dim3(512), 0, st, q, meta);
+    else if (rt_rows == 128) hipLaunchKernelGGL((k_attn_mfma<2, 2, false>), grid, dim3(512), 0, st, q, meta);
+    else hipLaunchKernelGGL((k_attn_mfma<2, 2, true>), grid, dim3(512), 0, st, q, meta);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (q.external_merge && !(p.debug_flags & 1)) {

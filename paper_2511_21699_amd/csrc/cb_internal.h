@@ -73,10 +73,12 @@ __device__ __forceinline__ int64_t slot_offset(const KvAddr& a, int seq, int slo
 // Ancestor sets of one tree built inside a workgroup (any block size >= 256; the first 256 threads
 // own one node each).  Section 3.2 of the paper: a tree token attends only to its ancestors (and, in
 // this library's reading, itself); anc[i] is the 256-bit set {i, parent(i), parent(parent(i)), ...}.
-// Pointer jumping: after r rounds a node knows its 2^r nearest ancestors, so eight rounds cover any
-// tree of up to 256 nodes whatever its depth.  `parent_of` is the node's sanitised parent (-1 at the
-// root) for threads < N.  On return anc_out[i][0..7] holds node i's set for every i < N and all
-// threads have passed a barrier.  The barriers are bare s_barrier instructions (LDS traffic is
+// Pointer jumping: after r rounds a node knows its 2^r nearest ancestors (itself included), so
+// jump_rounds(max_depth) rounds complete every node of depth <= max_depth, and eight rounds any
+// tree of up to 256 nodes.  `parent_of` is the node's sanitised parent (-1 at the root) for
+// threads < N.  On return anc[i][0..7] holds node i's set for every i < N, all threads have passed
+// a barrier, and the return value is the thread's remaining jump pointer: >= 0 exactly when its
+// node has more ancestors than the rounds could collect (its set is then incomplete).  The barriers are bare s_barrier instructions (LDS traffic is
 // ordered by explicit lgkmcnt waits), so the routine can run while global->LDS loads are in flight.
 struct AncScratch {
   uint32_t anc[CB_MAX_NODES][kAncWords];
@@ -87,7 +89,12 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 }
-__device__ __forceinline__ void build_ancestor_sets(AncScratch& sh, int N, int parent_of) {
+__host__ __device__ __forceinline__ int jump_rounds(int max_depth) {
+  int r = 0;
+  while (r < 8 && (1 << r) < max_depth + 1) r++;
+  return r;
+}
+__device__ __forceinline__ int build_ancestor_sets(AncScratch& sh, int N, int parent_of, int rounds) {
   const int t = threadIdx.x;
   uint32_t mine[kAncWords];
   int j = -1;
@@ -99,7 +106,7 @@ __device__ __forceinline__ void build_ancestor_sets(AncScratch& sh, int N, int p
     for (int w = 0; w < kAncWords; w++) sh.anc[t][w] = mine[w];
     sh.jump[t] = j;
   }
-  for (int r = 0; r < 8; r++) {
+  for (int r = 0; r < rounds; r++) {
     lds_barrier();
     uint32_t other[kAncWords];
     int jj = -1;
@@ -120,6 +127,7 @@ __device__ __forceinline__ void build_ancestor_sets(AncScratch& sh, int N, int p
     }
   }
   lds_barrier();
+  return j;
 }
 
 // Parent of node t of a tree as the kernels use it: -1 at the root, entries outside [0, t) become
@@ -153,6 +161,7 @@ struct AttnParams {
   int32_t xcd_remap;    // 1: renumber workgroups so that all splits of a tile run on one XCD
   int32_t grid_x, grid_y, grid_z;  // launch grid, repeated here so the kernel reads one argument block
   int32_t external_merge;  // 1: the kernel only writes partials; launch_attn_mfma runs a merge kernel afterwards
+  int32_t max_depth;    // deepest node the configuration allows (bounds the ancestor-set rounds)
   int32_t debug_flags;  // bit 0: skip the split merge (timing aid; output then undefined)
   int32_t* status;      // device status word (bit 4: a merge had to use cross-XCD loads)
   unsigned long long* dbg_ts;  // timing aid: 8 timestamps (100 MHz) per workgroup when debug bit 5 is set
@@ -170,10 +179,9 @@ hipError_t launch_tree_prepare(hipStream_t st, int batch, const SeqMeta& meta, c
 hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows, int64_t V,
                          ArgmaxPartial* partial, int nchunks, int batch, const SeqMeta& meta,
                          const int32_t* prep_parent, int max_depth, uint32_t* prep_anc, int32_t* status);
-hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
-                         const int32_t* tokens, int32_t* status, const ArgmaxPartial* partial,
-                         int nchunks, int max_depth, int32_t* argmax_out, int32_t* path,
-                         int32_t* len_ctx, int32_t* len_user, int32_t* tok_user);
+struct AcceptArgs;  // cb_logits.h
+struct LogitsWork;
+hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const AcceptArgs& args);
 hipError_t launch_compact(hipStream_t st, int batch, const SeqMeta& meta, const KvAddr* layers,
                           int num_layers, int Hkv, int D, int elem_bytes, int max_depth,
                           const int32_t* path, const int32_t* acc_len, int32_t* new_len);
@@ -182,7 +190,9 @@ hipError_t launch_attn_simt(hipStream_t st, const AttnParams& p, const SeqMeta& 
 hipError_t launch_merge(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype, int total_nodes);
 int attn_mfma_tile_rows(int mrows);            // rows per workgroup tile chosen for a given g*N
 bool attn_mfma_supports(const AttnParams& p);  // shape/geometry the MFMA kernel takes (bf16 is the caller's check)
+bool attn_mfma_can_fuse(const AttnParams& p, int max_nodes_in_call, int64_t logits_items, int logits_dtype);
+// with logits_work != nullptr (only if attn_mfma_can_fuse) the same launch also scans the logits and runs the acceptance
 hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
-                            int total_nodes);
+                            int total_nodes, const LogitsWork* logits_work);
 
 }  // namespace cb

@@ -1,6 +1,6 @@
 // Tree preparation (ancestor sets), vocabulary argmax, greedy acceptance and KV compaction kernels.
 // gfx950 only; 64-wide wavefronts are assumed throughout.
-#include "cb_internal.h"
+#include "cb_logits.h"
 
 namespace cb {
 
@@ -65,17 +65,8 @@ hipError_t launch_tree_prepare(hipStream_t st, int batch, const SeqMeta& meta, c
 
 // ------------------------------------------------------------------------------------------------
 // Argmax over the vocabulary: the token the model generates at a node is the first maximum of the
-// node's logits row.  One workgroup scans kArgmaxChunk elements with 16-byte loads; (value, index)
-// pairs are combined under the total order "larger value, then smaller index" at every level, so
-// equal maxima (common with bf16 logits) resolve to the lowest index exactly as a serial scan does.
+// node's logits row.  One workgroup scans kArgmaxChunk elements (scan_chunk() of cb_logits.h).
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ float elem_to_float(float x) { return x; }
-__device__ __forceinline__ float elem_to_float(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
-
-__device__ __forceinline__ void amax_take(float& bv, int& bi, float v, int i) {
-  if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-}
-
 // Rows [0, rows) of the grid's y dimension scan logits; when `prep` is set, rows [rows, rows + batch)
 // build the ancestor sets of one sequence each (x = 0 only), which saves a launch of their own.
 struct PrepareArgs {
@@ -96,65 +87,12 @@ __global__ __launch_bounds__(256) void k_argmax(const T* __restrict__ logits, in
       tree_prepare_block(prep_lds, meta, blockIdx.y - rows, prep.parent, prep.max_depth, prep.anc, prep.status);
     return;
   }
-  constexpr int VEC = 16 / sizeof(T);
-  constexpr int kVecPerThread = kArgmaxChunk / VEC / 256;
-  const int row = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
-  const int64_t start = (int64_t)c * kArgmaxChunk;
-  const int64_t end = (start + kArgmaxChunk < V) ? start + kArgmaxChunk : V;
-  const T* base = logits + (int64_t)row * V;
-  float bv = -INFINITY;
-  int bi = 0x7fffffff;
-  const bool aligned = ((reinterpret_cast<uintptr_t>(base + start)) & 15) == 0;
-  int64_t vec_end = start;
-  if (aligned) {
-    const int64_t nvec = (end - start) / VEC;
-    vec_end = start + nvec * VEC;
-    const uint4* vp = reinterpret_cast<const uint4*>(base + start);
-    uint4 u[kVecPerThread];  // all of the thread's loads are in flight together
-#pragma unroll
-    for (int k = 0; k < kVecPerThread; k++) {
-      const int64_t i = tid + k * 256;
-      u[k] = i < nvec ? vp[i] : uint4{0, 0, 0, 0};
-    }
-#pragma unroll
-    for (int k = 0; k < kVecPerThread; k++) {
-      const int64_t i = tid + k * 256;
-      if (i >= nvec) continue;
-      const int e0 = (int)(start + i * VEC);
-      if constexpr (sizeof(T) == 2) {
-        const uint32_t w[4] = {u[k].x, u[k].y, u[k].z, u[k].w};
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          amax_take(bv, bi, __uint_as_float(w[j] << 16), e0 + 2 * j);
-          amax_take(bv, bi, __uint_as_float(w[j] & 0xffff0000u), e0 + 2 * j + 1);
-        }
-      } else {
-        amax_take(bv, bi, __uint_as_float(u[k].x), e0);
-        amax_take(bv, bi, __uint_as_float(u[k].y), e0 + 1);
-        amax_take(bv, bi, __uint_as_float(u[k].z), e0 + 2);
-        amax_take(bv, bi, __uint_as_float(u[k].w), e0 + 3);
-      }
-    }
-  }
-  for (int64_t i = vec_end + tid; i < end; i += 256) amax_take(bv, bi, elem_to_float(base[i]), (int)i);
-  // wavefront, then workgroup
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) {
-    float ov = __shfl_xor(bv, s, 64);
-    int oi = __shfl_xor(bi, s, 64);
-    amax_take(bv, bi, ov, oi);
-  }
-  __shared__ float sv[4];
-  __shared__ int si[4];
-  if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
-  __syncthreads();
-  if (tid == 0) {
-    for (int w = 1; w < 4; w++) amax_take(bv, bi, sv[w], si[w]);
-    ArgmaxPartial r;
-    r.value = bv;
-    r.index = bi;
-    out[(int64_t)row * nchunks + c] = r;
-  }
+  __shared__ ScanLds scan_lds;
+  const int row = blockIdx.y, c = blockIdx.x;
+  float bv;
+  int bi;
+  scan_chunk<T, 256>(logits + (int64_t)row * V, V, c, threadIdx.x, scan_lds, bv, bi);
+  if (threadIdx.x == 0) amax_store<false>(out + (int64_t)row * nchunks + c, bv, bi);
 }
 
 hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows, int64_t V,
@@ -175,105 +113,22 @@ hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows
 }
 
 // ------------------------------------------------------------------------------------------------
-// Greedy acceptance (Section 3.2, last paragraphs).  A node is accepted when every non-root node on
-// its chain carries the token generated at that node's parent; with match = {x : tok[x] ==
-// a[parent(x)]} (root included) that is anc[c] being a subset of match.  The accepted node of
-// greatest depth wins (lowest index among equals); its ancestor set *is* the path, each member
-// sitting at position depth(member) = |anc(member)| - 1.
+// Greedy acceptance (Section 3.2, last paragraphs), one workgroup per sequence; the arithmetic is
+// accept_sequence() of cb_logits.h.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_accept(SeqMeta meta, const int32_t* __restrict__ parent,
-                                                const int32_t* __restrict__ tokens,
-                                                int32_t* status,
-                                                const ArgmaxPartial* __restrict__ partial, int nchunks,
-                                                int max_depth, int32_t* __restrict__ argmax_out,
-                                                int32_t* __restrict__ path, int32_t* len_ctx,
-                                                int32_t* len_user, int32_t* __restrict__ tok_user) {
-  __shared__ int sh_a[CB_MAX_NODES];
-  __shared__ AncScratch sh_anc;
-  __shared__ uint32_t sh_match[kAncWords];
-  __shared__ uint32_t sh_best[kAncWords];
-  __shared__ uint32_t sh_key[4];
-  const int b = blockIdx.x, t = threadIdx.x;
-  const int off = meta.node_off[b];
-  int N = meta.node_off[b + 1] - off;
-  N = N > CB_MAX_NODES ? CB_MAX_NODES : N;
-  int a = -1;
-  if (t < N) {
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    for (int c = 0; c < nchunks; c++) {
-      ArgmaxPartial r = partial[(int64_t)(off + t) * nchunks + c];
-      amax_take(bv, bi, r.value, r.index);
-    }
-    a = bi;
-    argmax_out[off + t] = a;
-  }
-  sh_a[t] = a;
-  __syncthreads();
-  bool match = false;
-  int par = -1;
-  if (t < N) {
-    par = sanitized_parent(parent, off, t, status);
-    match = (t == 0) || (tokens[off + t] == sh_a[par]);
-  }
-  build_ancestor_sets(sh_anc, N, par);  // (the attention kernels build their own; nothing is passed between them)
-  const unsigned long long bal = __ballot(match);
-  if ((t & 63) == 0) {
-    sh_match[(t >> 6) * 2] = (uint32_t)bal;
-    sh_match[(t >> 6) * 2 + 1] = (uint32_t)(bal >> 32);
-  }
-  __syncthreads();
-  uint32_t my[kAncWords];
-  int depth = -1;
-  bool acc = t < N;
-#pragma unroll
-  for (int w = 0; w < kAncWords; w++) {
-    my[w] = (t < N) ? sh_anc.anc[t][w] : 0u;
-    depth += __popc(my[w]);
-    acc = acc && ((my[w] & ~sh_match[w]) == 0u);
-  }
-  if (depth > max_depth) {
-    acc = false;
-    if (t < N) atomicOr(status, 2);
-  }
-  uint32_t key = acc ? ((uint32_t)(depth + 1) << 16) | (uint32_t)(0xffff - t) : 0u;
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) {
-    uint32_t o = __shfl_xor(key, s, 64);
-    key = o > key ? o : key;
-  }
-  if ((t & 63) == 0) sh_key[t >> 6] = key;
-  __syncthreads();
-  key = sh_key[0];
-  for (int w = 1; w < 4; w++) key = sh_key[w] > key ? sh_key[w] : key;
-  const int best = 0xffff - (int)(key & 0xffff);  // the root is always accepted, so key != 0
-  const int L = (int)(key >> 16) - 1;
-  if (t == best) {
-#pragma unroll
-    for (int w = 0; w < kAncWords; w++) sh_best[w] = my[w];
-  }
-  __syncthreads();
-  const int stride = max_depth + 1;
-  if (t < N && ((sh_best[t >> 5] >> (t & 31)) & 1u)) {
-    path[b * stride + depth] = t;
-    tok_user[b * stride + depth] = a;
-  }
-  if (t > L && t < stride) {
-    path[b * stride + t] = -1;
-    tok_user[b * stride + t] = -1;
-  }
-  if (t == 0) {
-    len_ctx[b] = L;
-    len_user[b] = L;
+__global__ __launch_bounds__(256) void k_accept(SeqMeta meta, AcceptArgs args) {
+  __shared__ AcceptLds sh;
+  const int b = blockIdx.x;
+  const int off = meta.node_off[b], N = meta.node_off[b + 1] - off;
+  if (N <= 64) {
+    if (threadIdx.x < 64) accept_wave<false>(args, b, off, N);
+  } else {
+    accept_sequence<false>(sh, args, b, off, N);
   }
 }
 
-hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
-                         const int32_t* tokens, int32_t* status, const ArgmaxPartial* partial,
-                         int nchunks, int max_depth, int32_t* argmax_out, int32_t* path,
-                         int32_t* len_ctx, int32_t* len_user, int32_t* tok_user) {
-  hipLaunchKernelGGL(k_accept, dim3(batch), dim3(256), 0, st, meta, parent, tokens, status, partial, nchunks,
-                     max_depth, argmax_out, path, len_ctx, len_user, tok_user);
+hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const AcceptArgs& args) {
+  hipLaunchKernelGGL(k_accept, dim3(batch), dim3(256), 0, st, meta, args);
   return hipGetLastError();
 }
 
