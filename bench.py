@@ -103,9 +103,14 @@ def main():
         return run, len(calls), "hipGraph"
 
     if args.traffic_probe:
-        ver.set_option("stages", 3)
+        # 50 launches of the step's dominant kernel: the one-launch verification where the library
+        # uses it, else the attention kernel alone
         bound_calls(False)[0]()
-        ver.set_option("stages", 2)
+        side.synchronize()
+        if not ver.last_launch_info()["fused"]:
+            ver.set_option("stages", 3)
+            bound_calls(False)[0]()
+            ver.set_option("stages", 2)
         calls = bound_calls(False)
         for i in range(50):
             calls[i % copies]()
@@ -115,7 +120,8 @@ def main():
         torch.cuda.synchronize()
         b.copy_(a)
         torch.cuda.synchronize()
-        print(json.dumps({"traffic_probe": True, "attention_launches": 50, "copy_bytes_each_way": a.numel()}))
+        print(json.dumps({"traffic_probe": True, "launches": 50, "fused": ver.last_launch_info()["fused"],
+                          "copy_bytes_each_way": a.numel()}))
         return
 
     # ---- whole step: W warm-up steps, then exactly K timed steps
@@ -131,6 +137,7 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
     accepted = d_len.cpu().tolist()
+    info = ver.last_launch_info()
 
     # ---- one stage alone (attention incl. its split merge; argmax), HIP events on the launch stream
     def timed_stage(mask):
@@ -152,7 +159,18 @@ def main():
 
     attn_us = timed_stage(2)
     argmax_us = timed_stage(4)
+    verify_us = timed_stage(15)          # attention + argmax + acceptance (no compaction): one launch when fused
     attn_gbps = attn_bytes / attn_us / 1e3
+    # The dominant kernel of the timed step.  Small calls run the whole verification as one launch
+    # (k_verify_mfma): its algorithmic bytes are the attention's plus the logits'.  Otherwise it is
+    # the attention kernel (with its split merge).
+    if info["fused"]:
+        roof_kernel = "cb::k_verify_mfma (tree attention incl. split merge + logits argmax + acceptance, one launch)"
+        roof_bytes, roof_us = attn_bytes + case.logits_bytes(), verify_us
+    else:
+        roof_kernel = "cb::k_attn_mfma (tree attention incl. split merge)" if info["impl"] == 2 else "cb::k_attn_simt + cb::k_merge"
+        roof_bytes, roof_us = attn_bytes, attn_us
+    roof_gbps = roof_bytes / roof_us / 1e3
 
     out = {
         "metric": "tree-verify attention HBM GB/s (% of peak) + verify steps/s, 7B shape",
@@ -177,11 +195,14 @@ def main():
         "attention_gbps": round(attn_gbps, 1),
         "attention_pct_hbm_peak": round(100 * attn_gbps / HBM_PEAK_GBPS, 2),
         "argmax_us": round(argmax_us, 3),
-        "roofline": {"bound": "hbm", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "kernel": "cb::k_attn_mfma (tree attention incl. split merge)", "algorithmic_bytes": attn_bytes},
+        "verify_us": round(verify_us, 3),
+        "one_launch_verify": info["fused"],
+        "splits": info["nsplit"],
+        "roofline": {"bound": "hbm", "achieved": round(roof_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(roof_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": roof_kernel, "algorithmic_bytes": roof_bytes, "launch_us": round(roof_us, 3)},
     }
-    traffic_file = os.path.join(ROOT, "profiles", "attention_traffic.json")
+    traffic_file = os.path.join(ROOT, "profiles", "dominant_kernel_traffic.json")
     if os.path.exists(traffic_file):
         try:
             out["roofline"]["traffic"] = json.load(open(traffic_file)).get(f"config{args.config}")

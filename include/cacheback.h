@@ -150,8 +150,8 @@ int cb_verify_tree(cb_ctx *ctx, void *hip_stream, int32_t batch, const void *q,
  *   d_accepted_len                  device [batch]
  *   d_accepted_tokens               device [batch][max_depth+1]
  * The tree's contents cannot be checked on the host here: a malformed parent entry is treated as
- * "child of the root", nodes deeper than max_depth are never accepted, and the status word returned
- * by cb_device_status becomes non-zero; nothing faults.
+ * "child of the root", nodes deeper than max_depth are never accepted (their attention rows are
+ * unspecified), and the status word returned by cb_device_status becomes non-zero; nothing faults.
  */
 int cb_verify_tree_device(cb_ctx *ctx, void *hip_stream, int32_t batch, const void *q,
                           const cb_kv_layer *kv, const int32_t *kv_len,
@@ -185,6 +185,9 @@ int cb_device_status(cb_ctx *ctx, int32_t *status);
  *                4 argmax, 8 acceptance; default 15) -- for timing one step in isolation; with a
  *                step left out the results of the call are those of an earlier call or undefined
  *   "parallel_scan"  1 = run the logits scan on the context's second stream beside the attention
+ *   "fuse_logits"    0 = never run the logits scan and the acceptance inside the attention launch
+ *                    (default 1: small calls -- MFMA attention, sequences of at most 64/g nodes, bf16
+ *                    logits, no more logits chunks than attention workgroups -- are one launch)
  *   "time_attention"  1 = record HIP events around the attention kernels (see cb_last_attention_ms) */
 int cb_set_option(cb_ctx *ctx, const char *name, int64_t value);
 
@@ -192,6 +195,12 @@ int cb_set_option(cb_ctx *ctx, const char *name, int64_t value);
  * events recorded around them on the call's stream); enabled with option "time_attention" = 1.
  * Synchronises.  Not available under stream capture. */
 int cb_last_attention_ms(cb_ctx *ctx, float *ms);
+
+/* How the last verify call was launched (host memory, no device access): info[0] = attention kernel
+ * family (1 scalar, 2 MFMA), info[1] = partial slots per output row, info[2] = keys per split,
+ * info[3] = 1 if the logits scan and the acceptance ran inside the attention launch, else 0.
+ * CB_ESTATE before the first verify call. */
+int cb_last_launch_info(cb_ctx *ctx, int32_t info[4]);
 
 /* Timing aid: with option "debug_flags" bit 5 (32) set, the MFMA attention kernel stamps eight
  * 100 MHz clock readings per workgroup (entry, arguments read, loads issued, first stage ready,

@@ -22,7 +22,7 @@ ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_E
 
 EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device",
            "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
-           "cb_last_attention_ms", "cb_debug_timestamps", "cb_last_error", "cb_destroy"]
+           "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_last_error", "cb_destroy"]
 
 
 class CbConfig(C.Structure):
@@ -67,6 +67,7 @@ def load():
     L.cb_get_argmax.argtypes = [vp, i32p]
     L.cb_device_status.argtypes = [vp, i32p]
     L.cb_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
+    L.cb_last_launch_info.argtypes = [vp, i32p]
     L.cb_last_attention_ms.argtypes = [vp, C.POINTER(C.c_float)]
     L.cb_debug_timestamps.argtypes = [vp, C.POINTER(C.c_uint64), C.c_int32]
     L.cb_last_error.argtypes = [vp]
@@ -246,6 +247,11 @@ class Verifier:
         out = np.zeros((workgroups, 8), dtype=np.uint64)
         self._raise(self.L.cb_debug_timestamps(self.ctx, out.ctypes.data_as(C.POINTER(C.c_uint64)), workgroups))
         return out
+
+    def last_launch_info(self) -> dict:
+        out = (C.c_int32 * 4)()
+        self._raise(self.L.cb_last_launch_info(self.ctx, out))
+        return dict(impl=out[0], nsplit=out[1], chunk=out[2], fused=bool(out[3]))
 
     def last_attention_ms(self) -> float:
         ms = C.c_float(0)

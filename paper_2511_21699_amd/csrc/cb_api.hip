@@ -99,6 +99,7 @@ struct cb_ctx {
   void* h_block;
   // state of the last verify
   bool have_verify;
+  int32_t launch_info[4];
   bool host_knows_len;
   int batch;
   int total_nodes;
@@ -333,6 +334,10 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   }
   if (fork) CB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
   if ((stages & 8) && !fused) CB_HIP(ctx, launch_accept(st, batch, meta, acc));
+  ctx->launch_info[0] = use_mfma ? 2 : 1;
+  ctx->launch_info[1] = plan.nsplit;
+  ctx->launch_info[2] = plan.chunk;
+  ctx->launch_info[3] = fused ? 1 : 0;
   ctx->meta = meta;
   ctx->batch = batch;
   ctx->total_nodes = total;
@@ -610,6 +615,13 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   else if (!strcmp(name, "parallel_scan")) ctx->opt_fork = value;
   else if (!strcmp(name, "fuse_logits")) ctx->opt_fuse = value;
   else return set_err(ctx, CB_EINVAL, "unknown option '%s'", name);
+  return CB_OK;
+}
+
+int cb_last_launch_info(cb_ctx* ctx, int32_t info[4]) {
+  if (!ctx || !info) return set_err(ctx, CB_EINVAL, "null argument");
+  if (!ctx->have_verify) return set_err(ctx, CB_ESTATE, "no verify call yet");
+  for (int i = 0; i < 4; i++) info[i] = ctx->launch_info[i];
   return CB_OK;
 }
 

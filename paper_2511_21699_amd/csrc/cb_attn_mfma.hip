@@ -21,6 +21,8 @@
 //   16(e/4)+4kg+e%4), A = V^T must hold the same keys for dim c of the 16-dim tile; it is fetched
 //   from the row-major V tile with ds_read_b64_tr_b16 (each 16-lane group reads a 4-key x 16-dim
 //   block and receives it transposed).  D[v] = O^T[dim 4kg+v][query c].
+#include <type_traits>
+
 #include "cb_logits.h"
 
 namespace cb {
@@ -529,41 +531,55 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     hook->stamp(2);
   }
 
-  if constexpr (G == 2 && !SEQ) {
-    // combine the two wave groups' softmax states: group 1 parks (o, mref, l) in the ring, group 0 adds it
+  // With two wave groups each group finishes one half of the head dimension: dim tiles
+  // [dt0, dt0 + ndt).  It parks the other half of its accumulators and its (mref, l) in the ring,
+  // and adds the partner's parked half to its own.
+  constexpr bool kTwoGroups = G == 2 && !SEQ;
+  const int dt0 = kTwoGroups ? 4 * gi : 0;
+  constexpr int ndt = kTwoGroups ? 4 : 8;
+  if constexpr (kTwoGroups) {
     __syncthreads();  // every wave is done with the ring
     const int lane = wi * 64 + l;
-    uint4* const park[4] = {K0, K1, K2, K3};  // 4 accumulator tiles x 256 lanes x 16 B each
     float2* const park_ml = reinterpret_cast<float2*>(V0);
-    if (gi == 1) {
+    // (the group index is a compile-time constant inside, so that ring slots and accumulators keep
+    // constant indices)
+    auto park_half = [&](auto gic) {
+      constexpr int GI = decltype(gic)::value;
+      uint4* const park[4] = {K0, K1, K2, K3};  // 16 accumulator tiles x 256 lanes x 16 B
 #pragma unroll
       for (int rr = 0; rr < R; rr++) {
 #pragma unroll
-        for (int dt = 0; dt < 8; dt++) {
+        for (int i = 0; i < 4; i++) {
+          const int dt = 4 * (1 - GI) + i;  // the partner's half
           const int slot = rr * 8 + dt;
           park[slot >> 2][(slot & 3) * 256 + lane] = __builtin_bit_cast(uint4, st.o[rr][dt]);
         }
-        park_ml[rr * 256 + lane] = float2{st.mref[rr], st.lacc[rr][0]};
+        park_ml[(GI * R + rr) * 256 + lane] = float2{st.mref[rr], st.lacc[rr][0]};
       }
-    }
-    __syncthreads();
-    if (gi == 0) {
+    };
+    auto take_half = [&](auto gic) {
+      constexpr int GI = decltype(gic)::value;
+      uint4* const park[4] = {K0, K1, K2, K3};
 #pragma unroll
       for (int rr = 0; rr < R; rr++) {
-        const float2 ml = park_ml[rr * 256 + lane];
-        const float m = fmaxf(st.mref[rr], ml.x);
+        const float2 ml2 = park_ml[((1 - GI) * R + rr) * 256 + lane];
+        const float m = fmaxf(st.mref[rr], ml2.x);
         const float mu = (m == -INFINITY) ? 0.f : m;
-        const float w0 = __builtin_amdgcn_exp2f((st.mref[rr] - mu) * c2), w1 = __builtin_amdgcn_exp2f((ml.x - mu) * c2);
+        const float w0 = __builtin_amdgcn_exp2f((st.mref[rr] - mu) * c2), w1 = __builtin_amdgcn_exp2f((ml2.x - mu) * c2);
 #pragma unroll
-        for (int dt = 0; dt < 8; dt++) {
+        for (int i = 0; i < 4; i++) {
+          const int dt = 4 * GI + i;
           const int slot = rr * 8 + dt;
           const floatx4 a = __builtin_bit_cast(floatx4, park[slot >> 2][(slot & 3) * 256 + lane]);
           st.o[rr][dt] = st.o[rr][dt] * w0 + a * w1;
         }
-        st.lacc[rr][0] = st.lacc[rr][0] * w0 + ml.y * w1;
+        st.lacc[rr][0] = st.lacc[rr][0] * w0 + ml2.y * w1;
         st.mref[rr] = m;
       }
-    }
+    };
+    if (gi == 0) park_half(std::integral_constant<int, 0>{}); else park_half(std::integral_constant<int, 1>{});
+    __syncthreads();
+    if (gi == 0) take_half(std::integral_constant<int, 0>{}); else take_half(std::integral_constant<int, 1>{});
   }
 
   if constexpr (kHookEarly) hook->stamp(3);
@@ -572,7 +588,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
       reinterpret_cast<char*>(p.partial) + seq_row0 * p.nsplit * kPartialBytes, 0, 0x7fffffff, 0x00020000);
   // finish.  Every lane holds its query's full denominator.
-  if (SEQ || gi == 0) {
+  {
 #pragma unroll
     for (int rr = 0; rr < R; rr++) {
       const float lt = st.lacc[rr][0];
@@ -581,10 +597,12 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
         const float inv = 1.0f / lt;
         CB_GLOBAL uint16_t* orow = gout + grow[rr] * D;
 #pragma unroll
-        for (int dt = 0; dt < 8; dt++) {
+        for (int i = 0; i < ndt; i++) {
+          const floatx4 o = (kTwoGroups && gi == 1) ? st.o[rr][(4 + i) & 7] : st.o[rr][i];
+          const int dt = dt0 + i;
           uintx2 pk;
-          pk[0] = (uint32_t)f2bf(st.o[rr][dt][0] * inv) | ((uint32_t)f2bf(st.o[rr][dt][1] * inv) << 16);
-          pk[1] = (uint32_t)f2bf(st.o[rr][dt][2] * inv) | ((uint32_t)f2bf(st.o[rr][dt][3] * inv) << 16);
+          pk[0] = (uint32_t)f2bf(o[0] * inv) | ((uint32_t)f2bf(o[1] * inv) << 16);
+          pk[1] = (uint32_t)f2bf(o[2] * inv) | ((uint32_t)f2bf(o[3] * inv) << 16);
           *(CB_GLOBAL uintx2*)(orow + 16 * dt + 4 * kg) = pk;
         }
       } else {
@@ -592,13 +610,15 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
         // workgroup, possibly on another XCD with its own L2, can read it without cache flushes
         const uint32_t pbyte = (uint32_t)(((grow[rr] - seq_row0) * p.nsplit + split) * kPartialBytes);
 #pragma unroll
-        for (int dt = 0; dt < 8; dt++) {
-          const uintx2 v = {(uint32_t)f2bf(st.o[rr][dt][0]) | ((uint32_t)f2bf(st.o[rr][dt][1]) << 16),
-                            (uint32_t)f2bf(st.o[rr][dt][2]) | ((uint32_t)f2bf(st.o[rr][dt][3]) << 16)};
+        for (int i = 0; i < ndt; i++) {
+          const floatx4 o = (kTwoGroups && gi == 1) ? st.o[rr][(4 + i) & 7] : st.o[rr][i];
+          const int dt = dt0 + i;
+          const uintx2 v = {(uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16),
+                            (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16)};
           if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, 0);
           else __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, kAgentCoherent);
         }
-        if (kg == 0) {
+        if (kg == 0 && (!kTwoGroups || gi == 0)) {
           // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
           const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
           const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};

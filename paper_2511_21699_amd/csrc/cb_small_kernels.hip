@@ -135,8 +135,9 @@ hipError_t launch_accept(hipStream_t st, int batch, const SeqMeta& meta, const A
 // ------------------------------------------------------------------------------------------------
 // KV compaction: slot S+j <- slot S+path[j], j = 1..L, for K and V of every kv head and layer.
 // path[j] >= j and the path is increasing, so slot S+j can be the source of an earlier step.  One
-// thread owns one 16-byte column (layer, K|V, head, offset in the row) and walks j upwards: every
-// read of a slot happens before the same thread overwrites it, and no other thread touches the column.
+// thread owns one 16-byte column (layer, K|V, head, offset in the row) and walks j upwards, eight
+// steps at a time: every read of a slot happens before the same thread overwrites it, and no other
+// thread touches the column.
 // ------------------------------------------------------------------------------------------------
 // The layers share their geometry; only the base pointers differ, so the kernel takes one KvAddr
 // and two pointer tables.
@@ -152,22 +153,48 @@ __global__ __launch_bounds__(256) void k_compact(SeqMeta meta, KvAddr geo, Layer
                                                  int32_t* __restrict__ new_len) {
   const int b = blockIdx.z;
   const int layer = blockIdx.y >> 1, which = blockIdx.y & 1;
-  const int S = meta.kv_len[b];
+  // the accepted length and the first path entries are requested together, before either is used
+  constexpr int kBatch = 8;
+  const int32_t* prow = path + b * (max_depth + 1);
   int L = acc_len[b];
+  int src[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; u++) src[u] = prow[1 + u <= max_depth ? 1 + u : max_depth];
+  const int S = meta.kv_len[b];
+  const int N = meta.node_off[b + 1] - meta.node_off[b];
   L = L < 0 ? 0 : (L > max_depth ? max_depth : L);
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) new_len[b] = S + L + 1;
   const int col = blockIdx.x * 256 + threadIdx.x;
   if (col >= Hkv * row_vecs) return;
   const int h = col / row_vecs, vec = col - h * row_vecs;
   char* base = reinterpret_cast<char*>(which ? ptrs.v[layer] : ptrs.k[layer]);
-  const int N = meta.node_off[b + 1] - meta.node_off[b];
-  for (int j = 1; j <= L; j++) {
-    int src = path[b * (max_depth + 1) + j];
-    if (src == j) continue;
-    if (src < j || src >= N) continue;  // cannot happen for a path produced by k_accept
-    const int64_t so = slot_offset(geo, b, S + src, h), doff = slot_offset(geo, b, S + j, h);
-    const uint4 x = *reinterpret_cast<const uint4*>(base + (so << elem_shift) + (int64_t)vec * 16);
-    *reinterpret_cast<uint4*>(base + (doff << elem_shift) + (int64_t)vec * 16) = x;
+  // Steps j0+1 .. j0+kBatch at a time: all of a batch's reads are issued before its first write.
+  // That is the serial order's result: step j reads slot S+path[j] >= S+j, which no earlier step
+  // (they write slots below S+j) has touched, so every read wants the slot's original contents.
+  for (int j0 = 0; j0 < L; j0 += kBatch) {
+    if (j0 > 0) {
+#pragma unroll
+      for (int u = 0; u < kBatch; u++) src[u] = prow[j0 + 1 + u <= max_depth ? j0 + 1 + u : max_depth];
+    }
+    uint4 x[kBatch];
+    bool live[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; u++) {
+      const int j = j0 + 1 + u;
+      // (src == j: nothing to move; src < j or >= N cannot happen for a path the acceptance produced)
+      live[u] = j <= L && src[u] > j && src[u] < N;
+      if (live[u]) {
+        const int64_t so = slot_offset(geo, b, S + src[u], h);
+        x[u] = *reinterpret_cast<const uint4*>(base + (so << elem_shift) + (int64_t)vec * 16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; u++) {
+      if (live[u]) {
+        const int64_t doff = slot_offset(geo, b, S + j0 + 1 + u, h);
+        *reinterpret_cast<uint4*>(base + (doff << elem_shift) + (int64_t)vec * 16) = x[u];
+      }
+    }
   }
 }
 

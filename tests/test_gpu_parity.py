@@ -236,3 +236,48 @@ def test_hip_graph_replays_match_eager_steps():
         for a, b in zip(results["eager"][rep], results["graph"][rep]):
             assert np.array_equal(a, b), f"replay {rep} differs from the eager step"
     assert results["eager"][0][3][0] >= 0
+
+
+@pytest.mark.parametrize("shape", ["7b", "ragged", "odd_vocab", "single_nodes"])
+def test_one_launch_verification_matches_separate_launches(shape):
+    """Small calls run attention, logits scan and acceptance as one launch; the same call with that
+    switched off uses three.  Both must give the oracle's results, and identical bits to each other."""
+    import torch
+    rng = np.random.default_rng(11)
+    opts, rows = {}, None
+    if shape == "7b":
+        case = W.make_config(2)
+        rows = sample_rows(case, 96)
+    elif shape == "ragged":       # short sequences leave whole splits without keys: those workgroups only scan logits
+        pars = [W.random_tree(rng, n, 4, 6, False)[0] for n in (64, 3, 33, 1)]
+        case = W.custom_case(111, "bf16", 4, 8, 8, 128, 20000, [1500, 10, 400, 0], pars, paged=True)
+        opts = {"splits": 12}     # 12 x 8 heads x 4 sequences workgroups for 101 rows x 3 chunks
+    elif shape == "odd_vocab":    # rows that are not 16-byte aligned and a ragged last chunk
+        case = W.custom_case(112, "bf16", 1, 16, 16, 128, 8193 + 6, [900], [W.random_tree(rng, 40, 4, 6, False)[0]])
+        opts = {"splits": 6}
+    else:
+        case = W.custom_case(113, "bf16", 3, 32, 8, 128, 300, [2000, 1, 77], [[-1], [-1], [-1]])
+    run_case(case, rows=rows, options=opts, what=f"one launch {shape}")
+    run_case(case, rows=rows, options=dict(opts, fuse_logits=0), what=f"separate launches {shape}")
+    dc = B.DeviceCase(case)
+    got = []
+    for fuse in (1, 0):
+        ver = B.Verifier(B.config_for_case(case))
+        for k, v in dict(opts, fuse_logits=fuse).items():
+            ver.set_option(k, v)
+        out, acc_len, acc_tok = ver.verify_tree(dc.q, dc.kv, case.kv_len, case.node_offsets, case.parent, case.tokens, dc.logits)
+        torch.cuda.synchronize()
+        assert ver.last_launch_info()["fused"] == bool(fuse), ver.last_launch_info()
+        got.append((B.to_host(out, "bf16").copy(), acc_len.copy(), acc_tok.copy(), ver.get_argmax(case.total_nodes), ver.get_path(case.B)))
+        ver.close()
+    for x, y in zip(got[0], got[1]):
+        assert np.array_equal(x, y)
+
+
+def test_large_calls_keep_separate_launches():
+    case = W.make_config(3, S=600)            # 128 nodes x 4 query heads per kv head: two row tiles per wave
+    dc = B.DeviceCase(case)
+    ver = B.Verifier(B.config_for_case(case))
+    ver.verify_tree(dc.q, dc.kv, case.kv_len, case.node_offsets, case.parent, case.tokens, dc.logits)
+    assert ver.last_launch_info()["fused"] is False and ver.last_launch_info()["impl"] == 2
+    ver.close()
