@@ -21,11 +21,11 @@ def kernels(db: str) -> str:
 
 def counters(db: str) -> str:
     c = sqlite3.connect(db)
-    rows = c.execute("select kernel_name, counter_name, count(*), avg(value) from counters_collection "
+    rows = c.execute("select kernel_name, counter_name, count(*), avg(value), max(value) from counters_collection "
                      "group by kernel_name, counter_name order by kernel_name, counter_name")
-    out = [f"{'kernel':60s} {'counter':24s} {'dispatches':>10s} {'mean value':>14s}"]
-    for k, cn, n, v in rows:
-        out.append(f"{k[:60]:60s} {cn:24s} {n:10d} {v:14.1f}")
+    out = [f"{'kernel':60s} {'counter':24s} {'dispatches':>10s} {'mean value':>14s} {'max value':>14s}"]
+    for k, cn, n, v, mx in rows:
+        out.append(f"{k[:60]:60s} {cn:24s} {n:10d} {v:14.1f} {mx:14.1f}")
     return "\n".join(out)
 
 
