@@ -122,11 +122,22 @@ struct WaveState {
 // swaps: v_permlane16_swap exchanges odd 16-lane rows of one operand with even rows of the other,
 // v_permlane32_swap the upper half of one with the lower half of the other, so two swaps of a
 // value with itself bring every lane its partners.
-__device__ __forceinline__ float quad_max(float x) {
+// max of two finite-or-infinite floats as a median with +inf: one v_med3_f32, where fmaxf() costs a
+// canonicalising v_max_f32 per operand first (the compiler cannot know that MFMA results are not
+// signalling NaNs; the inputs are finite by precondition, so they are not).
+// `pinf` is +inf in a register the compiler cannot see through (opaque_inf()): with a literal it
+// folds the median back into fmaxf.
+__device__ __forceinline__ float opaque_inf() {
+  float x = INFINITY;
+  asm("" : "+v"(x));
+  return x;
+}
+__device__ __forceinline__ float max2(float a, float b, float pinf) { return __builtin_amdgcn_fmed3f(a, b, pinf); }
+__device__ __forceinline__ float quad_max(float x, float pinf) {
   auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  x = max2(__uint_as_float(a[0]), __uint_as_float(a[1]), pinf);
   auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+  return max2(__uint_as_float(b[0]), __uint_as_float(b[1]), pinf);
 }
 
 constexpr float kRescaleSlack = 8.0f;  // log2 units the running maximum may exceed the reference
@@ -143,6 +154,7 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
                                               WaveState<R>& st, float c2, int key0, int S, int kend,
                                               bool need_mask, const uint32_t* anc_lds, const int* row_node, int l) {
   const int c = l & 15, kg = l >> 4;
+  const float pinf = opaque_inf();
   // all K operands of the stage are requested before the first MFMA, and all V operands before the
   // softmax arithmetic, so that LDS latency hides behind the matrix and vector work
   uint4 kraw[2][4];
@@ -216,8 +228,9 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
         x[e] = ((vis >> j) & 1u) ? x[e] : -INFINITY;
       }
     }
-    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mx = quad_max(mx);
+    float mx = max2(max2(max2(x[0], x[1], pinf), max2(x[2], x[3], pinf), pinf),
+                    max2(max2(x[4], x[5], pinf), max2(x[6], x[7], pinf), pinf), pinf);
+    mx = quad_max(mx, pinf);
     // lazy reference update; the decision is identical in the 4 lanes of a query
     const bool raise = (mx - st.mref[rr]) * c2 > kRescaleSlack;  // false when both are -inf (NaN)
     if (__builtin_amdgcn_ballot_w64(raise) != 0ull) {
@@ -245,6 +258,101 @@ __device__ __forceinline__ void compute_stage(const uint4* __restrict__ ks, cons
 #pragma unroll
     for (int rr = 0; rr < NV; rr++)
       st.o[rr][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[rr], st.o[rr][dt], 0, 0, 0);
+  }
+}
+
+// The same stage for a wave with two full row tiles and no key to mask (all keys in the cached
+// prefix and inside the split): the common case of long sweeps.  The two row tiles are independent
+// chains QK^T -> softmax -> PV; written one behind the other they leave the matrix cores idle during
+// the softmax and the vector ALU idle during the MFMAs.  Here the second tile's exponentials are
+// spread between the first tile's PV MFMAs (an MFMA occupies the matrix core for 16 cycles during
+// which the wave can issue independent vector instructions), and the row maxima of both tiles are
+// taken before a single, rarely taken rescale branch, so that everything after it is one basic block.
+__device__ __forceinline__ void compute_stage_pair(const uint4* __restrict__ ks, const uint4* __restrict__ vs,
+                                                   WaveState<2>& st, float c2, int l) {
+  const int c = l & 15, kg = l >> 4;
+  const float pinf = opaque_inf();
+  uint4 kraw[2][4];
+#pragma unroll
+  for (int sub = 0; sub < 2; sub++) {
+    const int row = 16 * sub + c;
+#pragma unroll
+    for (int ds = 0; ds < 4; ds++) kraw[sub][ds] = ks[row * 16 + ((kg + 4 * ds) ^ (row & 15))];
+  }
+  const char* vbytes = reinterpret_cast<const char*>(vs);
+  bf16x4 va[8][2];
+  auto read_v = [&](int dt) {
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      const int row = 16 * t + 4 * kg + (c >> 2);
+      const int piece = 2 * dt + ((c & 3) >> 1);
+      const int slot = piece ^ ((row & 7) << 1);
+      const char* addr = vbytes + row * 256 + slot * 16 + (c & 1) * 8;
+      va[dt][t] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(addr));
+    }
+  };
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++) read_v(dt);
+  // ---- scores of both tiles, tile 0 first so that its maximum can be taken under tile 1's MFMAs
+  floatx4 s[2][2];
+  float mx[2];
+#pragma unroll
+  for (int rr = 0; rr < 2; rr++) {
+    s[rr][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+    s[rr][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ds = 0; ds < 4; ds++) {
+#pragma unroll
+      for (int sub = 0; sub < 2; sub++)
+        s[rr][sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[sub][ds]), st.q[rr][ds], s[rr][sub], 0, 0, 0);
+    }
+  }
+  bool raise[2];
+#pragma unroll
+  for (int rr = 0; rr < 2; rr++) {
+    float m = max2(max2(max2(s[rr][0][0], s[rr][0][1], pinf), max2(s[rr][0][2], s[rr][0][3], pinf), pinf),
+                   max2(max2(s[rr][1][0], s[rr][1][1], pinf), max2(s[rr][1][2], s[rr][1][3], pinf), pinf), pinf);
+    mx[rr] = quad_max(m, pinf);
+    raise[rr] = (mx[rr] - st.mref[rr]) * c2 > kRescaleSlack;  // false when both are -inf (NaN)
+  }
+  if (__builtin_amdgcn_ballot_w64(raise[0] || raise[1]) != 0ull) {
+#pragma unroll
+    for (int rr = 0; rr < 2; rr++) {
+      const float alpha = raise[rr] ? __builtin_amdgcn_exp2f((st.mref[rr] - mx[rr]) * c2) : 1.0f;
+      if (raise[rr]) st.mref[rr] = mx[rr];
+#pragma unroll
+      for (int dt = 0; dt < 8; dt++) st.o[rr][dt] *= alpha;
+      st.lacc[rr] *= alpha;
+    }
+  }
+  // ---- one basic block from here on
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, uint4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+  const float nm0 = (st.mref[0] == -INFINITY) ? 0.f : -st.mref[0] * c2;
+  const float nm1 = (st.mref[1] == -INFINITY) ? 0.f : -st.mref[1] * c2;
+  union { bf16x8 v; __bf16 h[8]; } p0, p1;
+#pragma unroll
+  for (int e = 0; e < 8; e++) p0.h[e] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[0][e >> 2][e & 3], c2, nm0));
+  // (the scheduling barriers pin this interleaving: left alone, the instruction scheduler gathers all
+  // exponentials in front of the MFMAs)
+  __builtin_amdgcn_sched_barrier(0);
+  st.lacc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, p0.v, st.lacc[0], 0, 0, 0);
+  float e1[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; dt++) {
+    if (dt + 4 < 8) read_v(dt + 4);
+    const bf16x8 a = __builtin_shufflevector(va[dt][0], va[dt][1], 0, 1, 2, 3, 4, 5, 6, 7);
+    st.o[0][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, p0.v, st.o[0][dt], 0, 0, 0);
+    e1[dt] = __builtin_amdgcn_exp2f(fmaf(s[1][dt >> 2][dt & 3], c2, nm1));  // tile 1's softmax under tile 0's MFMAs
+    asm volatile("" : "+v"(e1[dt]));  // (the value is produced here, not sunk to its use after the loop)
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; e++) p1.h[e] = (__bf16)e1[e];
+  st.lacc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, p1.v, st.lacc[1], 0, 0, 0);
+#pragma unroll
+  for (int dt = 0; dt < 8; dt++) {
+    const bf16x8 a = __builtin_shufflevector(va[dt][0], va[dt][1], 0, 1, 2, 3, 4, 5, 6, 7);
+    st.o[1][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, p1.v, st.o[1][dt], 0, 0, 0);
   }
 }
 
@@ -494,6 +602,9 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 // the row tiles of a wave that lie past the sequence's rows are left out (R = 2: all, one or none)
 #define CB_COMPUTE(kp, vp, key0, need_mask)                                                                    \
   do {                                                                                                         \
+    if constexpr (R == 2) {                                                                                    \
+      if (nvt == R && !(need_mask)) { compute_stage_pair(kp, vp, st, c2, l); break; }                          \
+    }                                                                                                          \
     if (nvt == R) compute_stage<R, R>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);  \
     else if (R > 1) compute_stage<R, 1>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);\
   } while (0)
