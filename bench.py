@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--impl", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage-probe", type=int, default=0, metavar="N",
+                    help="for rocprofv3 --pmc runs: N launches of the attention stage alone on cold inputs, nothing else")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: 50 attention launches, then one 256 MiB device copy as the calibration kernel")
     args = ap.parse_args()
@@ -101,6 +103,17 @@ def main():
                 for _ in range(n):
                     graph.replay()
         return run, len(calls), "hipGraph"
+
+    if args.stage_probe:
+        ver.set_option("stages", 3)
+        bound_calls(False)[0]()            # ancestor sets in place (scalar path)
+        ver.set_option("stages", 2)
+        calls = bound_calls(False)
+        for i in range(args.stage_probe):
+            calls[i % copies]()
+            side.synchronize()
+        print(json.dumps({"stage_probe": True, "attention_launches": args.stage_probe, "config": args.config}))
+        return
 
     if args.traffic_probe:
         # 50 launches of the step's dominant kernel: the one-launch verification where the library
