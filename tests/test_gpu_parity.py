@@ -6,7 +6,7 @@ import pytest
 
 from paper_2511_21699_amd import binding as B
 from paper_2511_21699_amd import workloads as W
-from tests.gpu_harness import run_case, sample_rows
+from tests.gpu_harness import check_attention, run_case, sample_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -195,11 +195,15 @@ def test_error_paths_leave_outputs_alone():
     ver.close()
 
 
-def test_hip_graph_replays_match_eager_steps():
+@pytest.mark.parametrize("S", [700, 2048])
+def test_hip_graph_replays_match_eager_steps(S):
     """The benchmark replays captured steps: every replay of verify + compact must leave exactly what
-    the same steps leave when launched eagerly (compaction rewrites tree slots, so the state evolves)."""
+    the same steps leave when launched eagerly (compaction rewrites tree slots, so the state evolves).
+    S = 2048 is the benchmark's own workload and launch configuration (device-resident tree, one-launch
+    verification + compaction in a HIP graph); its first replay is also checked against the oracle."""
     import torch
-    case = W.make_config(2, S=700)
+    from oracle import cb_oracle as O
+    case = W.make_config(2, S=S)
     cfg = B.config_for_case(case)
     results = {}
     for mode in ("eager", "graph"):
@@ -236,6 +240,18 @@ def test_hip_graph_replays_match_eager_steps():
         for a, b in zip(results["eager"][rep], results["graph"][rep]):
             assert np.array_equal(a, b), f"replay {rep} differs from the eager step"
     assert results["eager"][0][3][0] >= 0
+    if S == 2048:
+        out0, k0, v0, len0, acc0 = results["graph"][0]
+        a_ref, res = O.verify(case)
+        L, path, toks = res[0]
+        assert len0[0] == L and acc0[0, :L + 1].tolist() == toks.tolist()
+        rows = sample_rows(case, 64, seed=3)
+        ref = O.attention_rows(case, rows)
+        got = W.to_f64(out0, "bf16")
+        check_attention(case, np.stack([got[case.node_offsets[b] + i, h] for b, h, i in rows]), ref, "graph replay, full size")
+        k_ref, v_ref = case.k.copy(), case.v.copy()
+        O.compact(case, k_ref, v_ref, 0, path)
+        assert np.array_equal(k0, k_ref) and np.array_equal(v0, v_ref)
 
 
 @pytest.mark.parametrize("shape", ["7b", "ragged", "odd_vocab", "single_nodes"])
