@@ -254,7 +254,7 @@ def test_hip_graph_replays_match_eager_steps(S):
         assert np.array_equal(k0, k_ref) and np.array_equal(v0, v_ref)
 
 
-@pytest.mark.parametrize("shape", ["7b", "ragged", "odd_vocab", "single_nodes"])
+@pytest.mark.parametrize("shape", ["7b", "ragged", "odd_vocab", "single_nodes", "many_splits"])
 def test_one_launch_verification_matches_separate_launches(shape):
     """Small calls run attention, logits scan and acceptance as one launch; the same call with that
     switched off uses three.  Both must give the oracle's results, and identical bits to each other."""
@@ -271,6 +271,9 @@ def test_one_launch_verification_matches_separate_launches(shape):
     elif shape == "odd_vocab":    # rows that are not 16-byte aligned and a ragged last chunk
         case = W.custom_case(112, "bf16", 1, 16, 16, 128, 8193 + 6, [900], [W.random_tree(rng, 40, 4, 6, False)[0]])
         opts = {"splits": 6}
+    elif shape == "many_splits":  # so many partials per tile that a separate merge kernel follows the launch
+        case = W.custom_case(114, "bf16", 1, 8, 8, 128, 1000, [6000], [W.random_tree(rng, 64, 4, 6, False)[0]], q_scale=2.0)
+        opts = {"splits": 24}
     else:
         case = W.custom_case(113, "bf16", 3, 32, 8, 128, 300, [2000, 1, 77], [[-1], [-1], [-1]])
     run_case(case, rows=rows, options=opts, what=f"one launch {shape}")
