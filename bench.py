@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--impl", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prefix", type=int, default=0, metavar="S",
+                    help="override the workload's cached prefix length (a scaling probe, not the headline workload)")
     ap.add_argument("--stage-probe", type=int, default=0, metavar="N",
                     help="for rocprofv3 --pmc runs: N launches of the attention stage alone on cold inputs, nothing else")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -56,7 +58,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    case = W.make_config(args.config)
+    case = W.make_config(args.config, **({"S": args.prefix} if args.prefix else {}))
     attn_bytes = case.attention_bytes()
     per_copy = attn_bytes + case.logits_bytes()
     copies = 1 if args.warm else (args.copies or max(2, -(-768 * 2 ** 20 // per_copy)))
