@@ -62,14 +62,14 @@ WsLayout ws_layout(const cb_config& c) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   L.anc = take(mt * kAncWords * 4);
-  L.parent = take(mt * 4);
-  L.tokens = take(mt * 4);
+  L.parent = take(mt * 4 * 2);  // staged tree of the host-array form: parents, then tokens right behind them
+  L.tokens = L.parent;         // (placed per call)
   L.amax_partial = take(mt * L.amax_chunks * sizeof(ArgmaxPartial));
   L.amax_out = take(mt * 4);
   L.path = take(c.max_batch * stride * 4);
   L.len_ctx = take(c.max_batch * 4);
-  L.res_len = take(c.max_batch * 4);
-  L.res_tok = take(c.max_batch * stride * 4);
+  L.res_len = take(c.max_batch * (1 + stride) * 4);  // results of the host-array form: lengths, then tokens right behind them
+  L.res_tok = L.res_len;                              // (placed per call)
   L.new_len = take(c.max_batch * 4);
   L.status = take(4);
   L.tickets = take((size_t)L.ticket_count * 4);
@@ -516,22 +516,23 @@ int cb_verify_tree(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int total = node_offsets[batch];
   const size_t stride = (size_t)ctx->cfg.max_depth + 1;
-  memcpy(ctx->h_parent, tree_parent, (size_t)total * 4);
-  memcpy(ctx->h_tokens, draft_tokens, (size_t)total * 4);
+  // one copy in (parents and tokens back to back), one copy out (lengths and tokens back to back)
+  int32_t* h_tree = ctx->h_parent;
+  memcpy(h_tree, tree_parent, (size_t)total * 4);
+  memcpy(h_tree + total, draft_tokens, (size_t)total * 4);
   int32_t* d_parent = ctx->dev<int32_t>(ctx->lay.parent);
-  int32_t* d_tokens = ctx->dev<int32_t>(ctx->lay.tokens);
-  CB_HIP(ctx, hipMemcpyAsync(d_parent, ctx->h_parent, (size_t)total * 4, hipMemcpyHostToDevice, st));
-  CB_HIP(ctx, hipMemcpyAsync(d_tokens, ctx->h_tokens, (size_t)total * 4, hipMemcpyHostToDevice, st));
+  int32_t* d_tokens = d_parent + total;
+  CB_HIP(ctx, hipMemcpyAsync(d_parent, h_tree, (size_t)total * 8, hipMemcpyHostToDevice, st));
   int32_t* d_len = ctx->dev<int32_t>(ctx->lay.res_len);
-  int32_t* d_tok = ctx->dev<int32_t>(ctx->lay.res_tok);
+  int32_t* d_tok = d_len + batch;
   rc = run_pipeline(ctx, st, batch, q, kv, kv_len, node_offsets, d_parent, d_tokens, logits, attn_out, d_len, d_tok);
   if (rc) return rc;
-  CB_HIP(ctx, hipMemcpyAsync(ctx->h_len, d_len, (size_t)batch * 4, hipMemcpyDeviceToHost, st));
-  CB_HIP(ctx, hipMemcpyAsync(ctx->h_tok, d_tok, (size_t)batch * stride * 4, hipMemcpyDeviceToHost, st));
+  int32_t* h_res = ctx->h_len;
+  CB_HIP(ctx, hipMemcpyAsync(h_res, d_len, (size_t)batch * (1 + stride) * 4, hipMemcpyDeviceToHost, st));
   CB_HIP(ctx, hipStreamSynchronize(st));
-  memcpy(accepted_len, ctx->h_len, (size_t)batch * 4);
-  memcpy(accepted_tokens, ctx->h_tok, (size_t)batch * stride * 4);
-  memcpy(ctx->last_len, ctx->h_len, (size_t)batch * 4);
+  memcpy(accepted_len, h_res, (size_t)batch * 4);
+  memcpy(accepted_tokens, h_res + batch, (size_t)batch * stride * 4);
+  memcpy(ctx->last_len, h_res, (size_t)batch * 4);
   ctx->host_knows_len = true;
   return CB_OK;
 }
