@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prefix", type=int, default=0, metavar="S",
                     help="override the workload's cached prefix length (a scaling probe, not the headline workload)")
+    ap.add_argument("--decode-loop", type=int, default=0, metavar="STEPS",
+                    help="instead of the headline: a closed decode loop (native drafter -> verify -> compact -> table "
+                         "update) of STEPS steps on the 7B shape with a stand-in target; prints its own JSON line")
     ap.add_argument("--stage-probe", type=int, default=0, metavar="N",
                     help="for rocprofv3 --pmc runs: N launches of the attention stage alone on cold inputs, nothing else")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -58,6 +61,10 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.decode_loop:
+        from paper_2511_21699_amd import decode_loop
+        print(json.dumps(decode_loop.run(steps=args.decode_loop, warmup=2000, **({"prompt_len": args.prefix} if args.prefix else {}))))
+        return
     case = W.make_config(args.config, **({"S": args.prefix} if args.prefix else {}))
     attn_bytes = case.attention_bytes()
     per_copy = attn_bytes + case.logits_bytes()

@@ -25,6 +25,10 @@ EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_att
            "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_last_error", "cb_destroy"]
 
 
+DRAFTER_EXPORTS = ["cbd_table_create", "cbd_table_destroy", "cbd_table_insert", "cbd_table_update", "cbd_table_query",
+                   "cbd_table_freeze", "cbd_table_size", "cbd_grow_tree"]
+
+
 class CbConfig(C.Structure):
     _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("qkv_dtype", C.c_int32), ("logits_dtype", C.c_int32), ("max_batch", C.c_int32),
@@ -70,6 +74,16 @@ def load():
     L.cb_last_launch_info.argtypes = [vp, i32p]
     L.cb_last_attention_ms.argtypes = [vp, C.POINTER(C.c_float)]
     L.cb_debug_timestamps.argtypes = [vp, C.POINTER(C.c_uint64), C.c_int32]
+    L.cbd_table_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(vp)]
+    L.cbd_table_destroy.argtypes = [vp]
+    L.cbd_table_destroy.restype = None
+    L.cbd_table_insert.argtypes = [vp, i32p, i32p]
+    L.cbd_table_update.argtypes = [vp, i32p, C.c_int64, C.c_int64]
+    L.cbd_table_query.argtypes = [vp, i32p, C.c_int32, i32p, i32p]
+    L.cbd_table_freeze.argtypes = [vp]
+    L.cbd_table_size.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.cbd_grow_tree.argtypes = [C.POINTER(vp), C.c_int32, i32p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                i32p, i32p, i32p, i32p]
     L.cb_last_error.argtypes = [vp]
     L.cb_last_error.restype = C.c_char_p
     L.cb_destroy.argtypes = [vp]
@@ -257,6 +271,112 @@ class Verifier:
         ms = C.c_float(0)
         self._raise(self.L.cb_last_attention_ms(self.ctx, C.byref(ms)))
         return ms.value
+
+
+# ----------------------------------------------------------------------------- host drafter (cacheback_drafter.h)
+class DraftTable:
+    """One leader -> follower cache table of the native drafter."""
+
+    def __init__(self, ll: int, fl: int, lc: int, fc: int):
+        self.L = load()
+        self.ll, self.fl, self.lc, self.fc = ll, fl, lc, fc
+        h = C.c_void_p()
+        rc = self.L.cbd_table_create(ll, fl, lc, fc, C.byref(h))
+        if rc:
+            raise CbError(rc, "cbd_table_create")
+        self.h = h
+        self._fol = (C.c_int32 * (fc * fl))()
+
+    def close(self):
+        if self.h:
+            self.L.cbd_table_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def insert(self, leader, follower):
+        a, b = _i32(leader), _i32(follower)
+        if len(a) != self.ll or len(b) != self.fl:
+            raise ValueError("leader/follower length mismatch")
+        rc = self.L.cbd_table_insert(self.h, _ip(a), _ip(b))
+        if rc:
+            raise CbError(rc, "cbd_table_insert")
+
+    def update(self, tokens, start: int = 0):
+        a = _i32(tokens)
+        rc = self.L.cbd_table_update(self.h, _ip(a), len(a), start)
+        if rc:
+            raise CbError(rc, "cbd_table_update")
+
+    def query(self, leader, refresh: bool = True):
+        a = _i32(leader)
+        if len(a) != self.ll:
+            raise ValueError("leader length mismatch")
+        n = C.c_int32(0)
+        rc = self.L.cbd_table_query(self.h, _ip(a), 1 if refresh else 0, self._fol, C.byref(n))
+        if rc:
+            raise CbError(rc, "cbd_table_query")
+        return [tuple(self._fol[i * self.fl:(i + 1) * self.fl]) for i in range(n.value)]
+
+    def freeze(self):
+        self.L.cbd_table_freeze(self.h)
+        return self
+
+    def size(self):
+        a, b = C.c_int64(0), C.c_int64(0)
+        self.L.cbd_table_size(self.h, C.byref(a), C.byref(b))
+        return a.value, b.value
+
+
+class TreeGrower:
+    """cbd_grow_tree with everything marshalled once: fixed tables, budget and output buffers.  `grow`
+    returns views of its own buffers (valid until the next call)."""
+
+    def __init__(self, tables, node_budget: int, depth_cap: int, crt: int = 0):
+        self._fn = load().cbd_grow_tree
+        self._tables = list(tables)
+        self._hs = (C.c_void_p * len(tables))(*[t.h for t in tables])
+        self._args = (len(tables),)
+        self._tail = (node_budget, depth_cap, crt)
+        self.parent = np.empty(node_budget, dtype=np.int32)
+        self.token = np.empty(node_budget, dtype=np.int32)
+        self.depth = np.empty(node_budget, dtype=np.int32)
+        self._out = (_ip(self.parent), _ip(self.token), _ip(self.depth))
+        self._n = C.c_int32(0)
+        self._nref = C.byref(self._n)
+        self._ctx_arr, self._ctx_ptr = None, None
+
+    def grow(self, context: np.ndarray, n_ctx: int):
+        """`context` is an int32 array whose first n_ctx entries are the text so far."""
+        if context is not self._ctx_arr:
+            if context.dtype != np.int32 or not context.flags.c_contiguous:
+                raise ValueError("context must be a contiguous int32 array")
+            self._ctx_arr, self._ctx_ptr = context, _ip(context)
+        rc = self._fn(self._hs, self._args[0], self._ctx_ptr, n_ctx, *self._tail, *self._out, self._nref)
+        if rc:
+            raise CbError(rc, "cbd_grow_tree")
+        n = self._n.value
+        return self.parent[:n], self.token[:n], self.depth[:n]
+
+
+def grow_tree(context, tables, node_budget: int, depth_cap: int, crt: int = 0):
+    """Native tree growth; returns int32 arrays (parent, token, depth)."""
+    L = load()
+    ctx = _i32(context)
+    hs = (C.c_void_p * len(tables))(*[t.h for t in tables])
+    par = np.empty(node_budget, dtype=np.int32)
+    tok = np.empty(node_budget, dtype=np.int32)
+    dep = np.empty(node_budget, dtype=np.int32)
+    n = C.c_int32(0)
+    rc = L.cbd_grow_tree(hs, len(tables), _ip(ctx), len(ctx), node_budget, depth_cap, crt, _ip(par), _ip(tok), _ip(dep),
+                         C.byref(n))
+    if rc:
+        raise CbError(rc, "cbd_grow_tree")
+    return par[:n.value], tok[:n.value], dep[:n.value]
 
 
 # ----------------------------------------------------------------------------- numpy <-> torch marshalling

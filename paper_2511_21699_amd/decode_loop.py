@@ -1,0 +1,162 @@
+"""Closed Cacheback decode loop on one GPU, without a language model.
+
+Every step of the paper's Section 3.2 runs for real -- the host drafter grows a tree from its LRU
+table, the GPU verifies it (tree attention, argmax, greedy acceptance), the accepted K/V is
+compacted, the table is updated over the new tokens by a sliding window -- except the model
+forward that would produce q/k/v and the logits.  A stand-in target takes its place:
+
+  * the "text the model would write" is a fixed synthetic token stream (truncated Zipf with copied
+    spans, the recipe of the benchmark workloads); at a tree node whose root path spells the
+    stream's continuation the target generates the stream's next token, at any other node a hash of
+    the node (such nodes can never be accepted, their output is irrelevant);
+  * logits are a fixed noise matrix in [-1, 1) with the generated token planted at 8.0 per node row;
+  * q and the K/V cache hold fixed random numbers (the attention runs at its real shape and cost,
+    its output is not consumed).
+
+Because verification is lossless (Section 2.2), the emitted tokens must equal the stream
+token for token whatever the drafter proposes; `run()` checks that after every step.
+
+    python -m paper_2511_21699_amd.decode_loop --steps 1000          # one JSON line
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import time
+
+import numpy as np
+
+from . import binding as B
+from . import drafter as PY
+from . import workloads as W
+
+
+def target_outputs(stream: np.ndarray, pos_root: int, parent, token, depth, vocab: int) -> np.ndarray:
+    """Token the stand-in target generates at every tree node (see the module text)."""
+    n = len(parent)
+    on = np.zeros(n, dtype=bool)
+    out = np.empty(n, dtype=np.int32)
+    for i in range(n):
+        on[i] = True if i == 0 else bool(on[parent[i]] and token[i] == stream[pos_root + depth[i]])
+        if on[i]:
+            out[i] = stream[pos_root + depth[i] + 1]
+        else:
+            out[i] = (int(token[i]) * 2654435761 + 40503 * int(depth[i]) + 977 * i) % vocab
+    return out
+
+
+def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_cap: int = 6, prompt_len: int = 2048,
+        Hq: int = 32, Hkv: int = 32, D: int = 128, vocab: int = 32000, ll: int = 2, fl: int = 3, lc: int = 8192,
+        fc: int = 4, seed: int = 7, device: str = "cuda:0", check_with=None, warmup: int = 50) -> dict:
+    """Runs `warmup` untimed and then `steps` timed decode steps; returns timings and acceptance statistics.
+
+    ``check_with(step, parent, token, logits_rows_host, accepted_tokens)`` is an optional callback for
+    tests (called for the first steps with the step's logits copied to the host)."""
+    import torch
+    rng = np.random.default_rng(seed)
+    room = (steps + warmup + 4) * (depth_cap + 1)
+    stream = W.zipf_stream(rng, prompt_len + room + 64, vocab)
+    gen = torch.Generator(device="cpu").manual_seed(seed)
+    cap = prompt_len + room + node_budget
+    dev = torch.device(device)
+    k = (torch.randn(1, cap, Hkv, D, generator=gen) / D ** 0.5).to(torch.bfloat16).to(dev)
+    v = (torch.randn(1, cap, Hkv, D, generator=gen) / D ** 0.5).to(torch.bfloat16).to(dev)
+    q = torch.randn(node_budget, Hq, D, generator=gen).to(torch.bfloat16).to(dev)
+    base = (torch.rand(node_budget, vocab, generator=gen) * 2 - 1).to(torch.bfloat16).to(dev)
+    logits = base.clone()
+    cfg = B.make_config(Hq, Hkv, D, "bf16", "bf16", 1, node_budget, depth_cap, vocab)
+    ver = B.Verifier(cfg, device=device)
+    kv = B.kv_layer(k, v)
+    if drafter == "native":
+        table = B.DraftTable(ll, fl, lc, fc)
+        grower = B.TreeGrower([table], node_budget, depth_cap)
+        grow = lambda text, n: grower.grow(text, n)
+        update = lambda toks, start: table.update(toks, start)
+    elif drafter == "python":
+        table = PY.CacheTable(ll, fl, lc, fc)
+        grow = lambda text, n: PY.grow_tree(text[:n], [table], node_budget, depth_cap)
+        update = lambda toks, start: table.update_sliding_window(toks, start)
+    else:
+        raise ValueError("drafter must be 'native' or 'python'")
+    emitted = np.empty(prompt_len + room + 8, dtype=np.int32)       # the whole text so far, prompt included
+    emitted[:prompt_len] = stream[:prompt_len]
+    n_text = prompt_len
+    update(emitted[:n_text], 0)                                     # prompt initialisation (Section 3.3)
+    t_draft = t_target = t_verify = t_compact = t_update = 0.0
+    accepted_total, nodes_total, text0 = 0, 0, prompt_len
+    kv_len = np.asarray([n_text - 1], dtype=np.int32)               # the root token's K/V is not cached yet
+    torch.cuda.synchronize(dev)
+    wall0 = time.perf_counter()
+    try:
+        for step in range(-warmup, steps):
+            if step == 0:                                           # the timed part starts here
+                torch.cuda.synchronize(dev)
+                t_draft = t_target = t_verify = t_compact = t_update = 0.0
+                accepted_total, nodes_total, text0 = 0, 0, n_text
+                wall0 = time.perf_counter()
+            t0 = time.perf_counter()
+            parent, token, depth = grow(emitted, n_text)
+            t1 = time.perf_counter()
+            parent = np.asarray(parent, dtype=np.int32)
+            token = np.asarray(token, dtype=np.int32)
+            n = len(parent)
+            # ---- stand-in for the model forward: logits rows for the tree's nodes
+            outs = target_outputs(stream, n_text - 1, parent, token, depth, vocab)
+            logits[:n].copy_(base[:n])
+            logits[torch.arange(n, device=dev), torch.from_numpy(outs).to(dev).long()] = 8.0
+            torch.cuda.synchronize(dev)
+            t2 = time.perf_counter()
+            kv_len[0] = n_text - 1
+            _, acc_len, acc_tok = ver.verify_tree(q[:n], kv, kv_len, [0, n], parent, token, logits[:n])
+            t3 = time.perf_counter()
+            ver.compact_kv([kv], 1)
+            t4 = time.perf_counter()
+            L = int(acc_len[0])
+            new = acc_tok[0, :L + 1]
+            if check_with is not None:
+                check_with(step + warmup, parent, token, logits[:n], new)
+            if not np.array_equal(new, stream[n_text:n_text + L + 1]):
+                raise AssertionError(f"step {step}: emitted {new.tolist()} but the text continues "
+                                     f"{stream[n_text:n_text + L + 1].tolist()} (verification must be lossless)")
+            emitted[n_text:n_text + L + 1] = new
+            old = n_text
+            n_text += L + 1
+            t5 = time.perf_counter()
+            update(emitted[:n_text], old - (fl - 1))               # every window that touches a new token
+            t6 = time.perf_counter()
+            t_draft += t1 - t0; t_target += t2 - t1; t_verify += t3 - t2; t_compact += t4 - t3; t_update += t6 - t5
+            accepted_total += L
+            nodes_total += n
+        torch.cuda.synchronize(dev)
+        wall = time.perf_counter() - wall0
+    finally:
+        ver.close()
+        if drafter == "native":
+            table.close()
+    us = lambda t: round(t / steps * 1e6, 2)
+    own = t_draft + t_verify + t_compact + t_update                 # everything except the stand-in target
+    return {"steps": steps, "drafter": drafter, "warmup": warmup, "tokens_emitted": int(n_text - text0),
+            "mean_accepted_tokens_per_step": round((n_text - text0) / steps, 3),
+            "mean_tree_nodes": round(nodes_total / steps, 1),
+            "draft_us": us(t_draft), "verify_us": us(t_verify), "compact_us": us(t_compact), "table_update_us": us(t_update),
+            "stand_in_target_us": us(t_target),
+            "steps_per_s_without_target": round(steps / own, 1), "steps_per_s_wall": round(steps / wall, 1),
+            "lossless": True,
+            "shape": f"Hq={Hq} Hkv={Hkv} D={D} V={vocab} prompt={prompt_len} TDL={node_budget} depth<={depth_cap} "
+                     f"LL={ll} FL={fl} LC={lc} FC={fc}"}
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--drafter", default="native", choices=["native", "python"])
+    ap.add_argument("--prompt", type=int, default=2048)
+    ap.add_argument("--nodes", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=2000, help="untimed steps first (the GPU takes a few tenths of a second to settle)")
+    args = ap.parse_args()
+    print(json.dumps(run(steps=args.steps, drafter=args.drafter, prompt_len=args.prompt, node_budget=args.nodes,
+                         warmup=args.warmup)))
+
+
+if __name__ == "__main__":
+    main()
