@@ -40,6 +40,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prefix", type=int, default=0, metavar="S",
                     help="override the workload's cached prefix length (a scaling probe, not the headline workload)")
+    ap.add_argument("--layers", type=int, default=0, metavar="L",
+                    help="instead of the headline: one step of an L-layer model -- tree attention on L distinct caches, "
+                         "one logits scan + acceptance, one compaction of all L layers -- captured as one HIP graph")
     ap.add_argument("--decode-loop", type=int, default=0, metavar="STEPS",
                     help="instead of the headline: a closed decode loop (native drafter -> verify -> compact -> table "
                          "update) of STEPS steps on the 7B shape with a stand-in target; prints its own JSON line")
@@ -70,6 +73,8 @@ def main():
     per_copy = attn_bytes + case.logits_bytes()
     copies = 1 if args.warm else (args.copies or max(2, -(-768 * 2 ** 20 // per_copy)))
     copies = max(1, min(copies, int(160e9 // per_copy)))
+    if args.layers:
+        copies = 1                       # the layers' distinct caches are the rotating inputs
     dcs = [B.DeviceCase(case, layout=args.layout) for _ in range(copies)]
     ver = B.Verifier(B.config_for_case(case, max_splits=72 if args.config == 4 else 0))
     if args.splits:
@@ -112,6 +117,43 @@ def main():
                 for _ in range(n):
                     graph.replay()
         return run, len(calls), "hipGraph"
+
+    if args.layers:
+        nl = args.layers
+        base = dcs[0]
+        ks = [base.k] + [torch.randn_like(base.k) * (case.D ** -0.5) for _ in range(nl - 1)]
+        vs = [base.v] + [torch.randn_like(base.v) * (case.D ** -0.5) for _ in range(nl - 1)]
+        qs = [base.q] + [torch.randn_like(base.q) for _ in range(nl - 1)]
+        layer_outs = [torch.empty_like(base.q) for _ in range(nl)]
+        paged = case.block_size > 0
+        kvs = [B.kv_layer(k, v, base.block_table, layout=args.layout, paged=paged) for k, v in zip(ks, vs)]
+        step = ver.bind_model_step(qs, kvs, case.kv_len, case.node_offsets, d_par, d_tok, base.logits, layer_outs,
+                                   d_len, d_acc, stream=side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+            for _ in range(max(1, args.warmup // 10)):
+                graph.replay()
+            side.synchronize()
+            n = max(1, args.steps // 10)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(side)
+            for _ in range(n):
+                graph.replay()
+            e1.record(side)
+            e1.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        total_bytes = nl * attn_bytes + case.logits_bytes()
+        print(json.dumps({"model_step": True, "layers": nl, "steps": n, "ms_per_step": round(ms, 4),
+                          "steps_per_s": round(1e3 / ms, 1), "us_per_layer": round(ms * 1e3 / nl, 2),
+                          "algorithmic_gbps": round(total_bytes / ms / 1e6, 1),
+                          "pct_hbm_peak": round(100 * total_bytes / ms / 1e6 / HBM_PEAK_GBPS, 2),
+                          "workload": f"configs[{args.config - 1}] {case.name} x {nl} layers, distinct caches ({nl * attn_bytes / 1e9:.2f} GB per step)",
+                          "launch": "hipGraph", "accepted_len": d_len.cpu().tolist()[:4]}))
+        return
 
     if args.stage_probe:
         ver.set_option("stages", 3)

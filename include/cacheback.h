@@ -160,6 +160,17 @@ int cb_verify_tree_device(cb_ctx *ctx, void *hip_stream, int32_t batch, const vo
                           int32_t *d_accepted_len, int32_t *d_accepted_tokens);
 
 /*
+ * Tree attention alone (Section 3.2: every node attends to the cached prefix, its ancestors and
+ * itself), for the layers of a model below the last one: the arguments of cb_verify_tree_device
+ * without tokens, logits and results.  Launches only; leaves the state of the last verify call
+ * (what cb_compact_kv, cb_get_path and cb_get_argmax refer to) untouched.
+ */
+int cb_tree_attention_device(cb_ctx *ctx, void *hip_stream, int32_t batch, const void *q,
+                             const cb_kv_layer *kv, const int32_t *kv_len,
+                             const int32_t *node_offsets, const int32_t *d_tree_parent,
+                             void *attn_out);
+
+/*
  * Moves the K/V of the path accepted by the last verify call of this context into place, for
  * `num_layers` caches that share one geometry (capacity, block table, layout) and differ only in
  * their k/v pointers: for j = 1..L_b, slot S_b+j <- slot S_b+path_b[j].  Enqueues on `hip_stream`.

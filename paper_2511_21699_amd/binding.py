@@ -20,7 +20,7 @@ CB_OK, CB_EINVAL, CB_ETREE, CB_ECAP, CB_ESTATE, CB_EHIP = range(6)
 CB_LAYOUT_TOKEN_MAJOR, CB_LAYOUT_HEAD_MAJOR = 0, 1
 ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_ESTATE", 5: "CB_EHIP"}
 
-EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device",
+EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device", "cb_tree_attention_device",
            "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
            "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_last_error", "cb_destroy"]
 
@@ -66,6 +66,7 @@ def load():
     L.cb_plan_attention.argtypes = [C.POINTER(CbConfig), C.c_int32, i32p, i32p, C.c_int32, i32p]
     L.cb_verify_tree.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, i32p, i32p, vp, vp, i32p, i32p]
     L.cb_verify_tree_device.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, vp, vp, vp, vp, vp, vp]
+    L.cb_tree_attention_device.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, vp, vp]
     L.cb_compact_kv.argtypes = [vp, vp, C.c_int32, C.POINTER(CbKvLayer), i32p]
     L.cb_get_path.argtypes = [vp, i32p]
     L.cb_get_argmax.argtypes = [vp, i32p]
@@ -210,6 +211,41 @@ class Verifier:
                                           logits.data_ptr(), attn_out.data_ptr(), d_acc_len.data_ptr(),
                                           d_acc_tok.data_ptr())
         self._raise(rc)
+
+    def tree_attention_device(self, q, kv: CbKvLayer, kv_len, node_offsets, d_parent, attn_out, stream=None):
+        """Tree attention alone (a model's layers below the last): enqueues launches only."""
+        kv_len, node_offsets = _i32(kv_len), _i32(node_offsets)
+        rc = self.L.cb_tree_attention_device(self.ctx, self._stream(stream), kv_len.shape[0], q.data_ptr(), C.byref(kv),
+                                             _ip(kv_len), _ip(node_offsets), d_parent.data_ptr(), attn_out.data_ptr())
+        self._raise(rc)
+
+    def bind_model_step(self, qs, kvs, kv_len, node_offsets, d_parent, d_tokens, logits, attn_outs, d_acc_len, d_acc_tok,
+                        stream=None):
+        """Pre-marshalled step of a whole model: tree attention for every layer (the last one inside the
+        verification call, which also scans the logits and accepts), then one compaction of all layers.
+        Returns a zero-argument callable that only makes the C calls."""
+        kv_len, node_offsets = _i32(kv_len), _i32(node_offsets)
+        st = self._stream(stream)
+        nl = len(kvs)
+        arr = (CbKvLayer * nl)(*kvs)
+        b = kv_len.shape[0]
+        att = [(self.ctx, st, b, qs[i].data_ptr(), C.byref(arr[i]), _ip(kv_len), _ip(node_offsets), d_parent.data_ptr(),
+                attn_outs[i].data_ptr()) for i in range(nl - 1)]
+        last = (self.ctx, st, b, qs[-1].data_ptr(), C.byref(arr[nl - 1]), _ip(kv_len), _ip(node_offsets),
+                d_parent.data_ptr(), d_tokens.data_ptr(), logits.data_ptr(), attn_outs[-1].data_ptr(),
+                d_acc_len.data_ptr(), d_acc_tok.data_ptr())
+        keep = (kv_len, node_offsets, arr, qs, kvs, logits, attn_outs)
+        attention, verify, compact = self.L.cb_tree_attention_device, self.L.cb_verify_tree_device, self.L.cb_compact_kv
+
+        def call(_keep=keep):
+            rc = 0
+            for a in att:
+                rc = rc or attention(*a)
+            rc = rc or verify(*last)
+            rc = rc or compact(self.ctx, st, nl, arr, None)
+            if rc:
+                self._raise(rc)
+        return call
 
     def bind_step(self, q, kv: CbKvLayer, kv_len, node_offsets, d_parent, d_tokens, logits, attn_out, d_acc_len,
                   d_acc_tok, layers: Sequence[CbKvLayer], stream=None):

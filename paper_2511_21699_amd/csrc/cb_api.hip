@@ -236,7 +236,8 @@ int check_common(cb_ctx* ctx, int32_t batch, const void* q, const cb_kv_layer* k
 // Enqueues the whole verification on `st`; the tree is already on the device.
 int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb_kv_layer* kv,
                  const int32_t* kv_len, const int32_t* node_offsets, const int32_t* d_parent,
-                 const int32_t* d_tokens, const void* logits, void* attn_out, int32_t* d_len, int32_t* d_tok) {
+                 const int32_t* d_tokens, const void* logits, void* attn_out, int32_t* d_len, int32_t* d_tok,
+                 int64_t stage_mask = 15) {
   const cb_config& c = ctx->cfg;
   SeqMeta meta{};
   for (int b = 0; b < batch; b++) meta.kv_len[b] = kv_len[b];
@@ -264,7 +265,9 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.debug_flags = (int32_t)ctx->opt_debug;
   ap.max_depth = c.max_depth;
 
-  const int64_t stages = ctx->opt_stages;  // measurement aid: bit 0 ancestor sets, 1 attention, 2 argmax, 3 acceptance
+  // bit 0 ancestor sets, 1 attention, 2 argmax, 3 acceptance; the option is a measurement aid, the
+  // mask is what the entry point asks for (cb_tree_attention_device: the first two)
+  const int64_t stages = ctx->opt_stages & stage_mask;
   const bool use_mfma = plan.impl == 2 && attn_mfma_supports(ap);
   // The logits scan does not depend on the attention, and the MFMA attention builds the ancestor sets
   // it needs itself, so with option "parallel_scan" the scan runs beside it on the context's second
@@ -334,6 +337,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   }
   if (fork) CB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
   if ((stages & 8) && !fused) CB_HIP(ctx, launch_accept(st, batch, meta, acc));
+  if (!(stage_mask & 8)) return CB_OK;  // attention alone leaves the state of the last verification as it is
   ctx->launch_info[0] = use_mfma ? 2 : 1;
   ctx->launch_info[1] = plan.nsplit;
   ctx->launch_info[2] = plan.chunk;
@@ -344,6 +348,23 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ctx->last_stream = st;
   ctx->have_verify = true;
   ctx->host_knows_len = false;
+  return CB_OK;
+}
+
+// Shapes are host data in the device-resident forms too: everything except the tree's contents is checked.
+int check_device_shapes(cb_ctx* ctx, int32_t batch, const cb_kv_layer* kv, const int32_t* kv_len, const int32_t* node_offsets) {
+  const cb_config& c = ctx->cfg;
+  if (!kv->k || !kv->v || kv->capacity_or_num_blocks < 1) return set_err(ctx, CB_EINVAL, "bad cache descriptor");
+  if (c.block_size > 0 && (!kv->block_table || kv->max_blocks_per_seq < 1)) return set_err(ctx, CB_EINVAL, "paged cache without a block table");
+  if (node_offsets[0] != 0) return set_err(ctx, CB_EINVAL, "node_offsets[0] must be 0");
+  for (int b = 0; b < batch; b++) {
+    const int64_t n = (int64_t)node_offsets[b + 1] - node_offsets[b];
+    if (n < 1) return set_err(ctx, CB_EINVAL, "sequence %d has no root node", b);
+    if (n > c.max_nodes) return set_err(ctx, CB_ECAP, "sequence %d has %lld nodes, max_nodes is %d", b, (long long)n, c.max_nodes);
+    if (kv_len[b] < 0) return set_err(ctx, CB_EINVAL, "negative kv_len[%d]", b);
+    const int64_t room = c.block_size > 0 ? (int64_t)kv->max_blocks_per_seq * c.block_size : kv->capacity_or_num_blocks;
+    if (kv_len[b] + n > room || kv_len[b] + n > (1ll << 30)) return set_err(ctx, CB_ECAP, "sequence %d does not fit the cache", b);
+  }
   return CB_OK;
 }
 
@@ -486,21 +507,25 @@ int cb_verify_tree_device(cb_ctx* ctx, void* hip_stream, int32_t batch, const vo
   ctx->err[0] = 0;
   if (!d_tree_parent || !d_draft_tokens || !d_accepted_len || !d_accepted_tokens)
     return set_err(ctx, CB_EINVAL, "null argument");
-  // shapes are host data in this form too: check everything except the tree's contents
-  const cb_config& c = ctx->cfg;
-  if (!kv->k || !kv->v || kv->capacity_or_num_blocks < 1) return set_err(ctx, CB_EINVAL, "bad cache descriptor");
-  if (c.block_size > 0 && (!kv->block_table || kv->max_blocks_per_seq < 1)) return set_err(ctx, CB_EINVAL, "paged cache without a block table");
-  if (node_offsets[0] != 0) return set_err(ctx, CB_EINVAL, "node_offsets[0] must be 0");
-  for (int b = 0; b < batch; b++) {
-    const int64_t n = (int64_t)node_offsets[b + 1] - node_offsets[b];
-    if (n < 1) return set_err(ctx, CB_EINVAL, "sequence %d has no root node", b);
-    if (n > c.max_nodes) return set_err(ctx, CB_ECAP, "sequence %d has %lld nodes, max_nodes is %d", b, (long long)n, c.max_nodes);
-    if (kv_len[b] < 0) return set_err(ctx, CB_EINVAL, "negative kv_len[%d]", b);
-    const int64_t room = c.block_size > 0 ? (int64_t)kv->max_blocks_per_seq * c.block_size : kv->capacity_or_num_blocks;
-    if (kv_len[b] + n > room || kv_len[b] + n > (1ll << 30)) return set_err(ctx, CB_ECAP, "sequence %d does not fit the cache", b);
-  }
+  rc = check_device_shapes(ctx, batch, kv, kv_len, node_offsets);
+  if (rc) return rc;
   return run_pipeline(ctx, static_cast<hipStream_t>(hip_stream), batch, q, kv, kv_len, node_offsets, d_tree_parent,
                       d_draft_tokens, logits, attn_out, d_accepted_len, d_accepted_tokens);
+}
+
+int cb_tree_attention_device(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, const cb_kv_layer* kv,
+                             const int32_t* kv_len, const int32_t* node_offsets, const int32_t* d_tree_parent,
+                             void* attn_out) {
+  if (!ctx) return set_err(nullptr, CB_EINVAL, "null context");
+  ctx->err[0] = 0;
+  if (!q || !kv || !kv_len || !node_offsets || !d_tree_parent || !attn_out) return set_err(ctx, CB_EINVAL, "null argument");
+  if (batch < 1 || batch > ctx->cfg.max_batch) return set_err(ctx, CB_EINVAL, "batch %d outside [1, %d]", batch, ctx->cfg.max_batch);
+  if (((uintptr_t)q | (uintptr_t)kv->k | (uintptr_t)kv->v | (uintptr_t)attn_out) & 15)
+    return set_err(ctx, CB_EINVAL, "device pointers must be 16-byte aligned");
+  const int rc = check_device_shapes(ctx, batch, kv, kv_len, node_offsets);
+  if (rc) return rc;
+  return run_pipeline(ctx, static_cast<hipStream_t>(hip_stream), batch, q, kv, kv_len, node_offsets, d_tree_parent,
+                      nullptr, nullptr, attn_out, nullptr, nullptr, 3);
 }
 
 int cb_verify_tree(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, const cb_kv_layer* kv,

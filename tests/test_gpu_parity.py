@@ -300,3 +300,56 @@ def test_large_calls_keep_separate_launches():
     ver.verify_tree(dc.q, dc.kv, case.kv_len, case.node_offsets, case.parent, case.tokens, dc.logits)
     assert ver.last_launch_info()["fused"] is False and ver.last_launch_info()["impl"] == 2
     ver.close()
+
+
+@pytest.mark.parametrize("kind", ["mfma", "scalar"])
+def test_model_step_of_several_layers(kind):
+    """cb_tree_attention_device for the lower layers, cb_verify_tree_device on the last, one cb_compact_kv
+    over all layers: every layer's attention against the oracle, the acceptance, and every layer's cache."""
+    import copy
+    import torch
+    from oracle import cb_oracle as O
+    rng = np.random.default_rng(21)
+    pars = [W.random_tree(rng, 40, 3, 6, False)[0], W.chain_tree(12)]
+    if kind == "mfma":
+        case = W.custom_case(121, "bf16", 2, 8, 4, 128, 700, [900, 130], pars, paged=True, p_match=0.8)
+    else:
+        case = W.custom_case(122, "f32", 2, 4, 2, 64, 700, [300, 50], pars, p_match=0.8)
+    nl = 3
+    layers = []
+    for i in range(nl):
+        c = copy.copy(case)
+        if i:
+            sub = W.custom_case(130 + i, case.dtype, 2, case.Hq, case.Hkv, case.D, 16, case.kv_len, pars, paged=case.block_size > 0)
+            c.q, c.k, c.v = sub.q, sub.k, sub.v
+            if case.block_size:
+                assert sub.k.shape == case.k.shape
+        layers.append(c)
+    dcs = [B.DeviceCase(c) for c in layers]
+    for dc in dcs[1:]:
+        dc.block_table = dcs[0].block_table            # the layers share one geometry
+    kvs = [B.kv_layer(dc.k, dc.v, dcs[0].block_table, paged=case.block_size > 0) for dc in dcs]
+    for c in layers[1:]:
+        c.block_table = case.block_table
+    ver = B.Verifier(B.config_for_case(case))
+    d_par = torch.from_numpy(case.parent).cuda(); d_tok = torch.from_numpy(case.tokens).cuda()
+    outs = [torch.zeros_like(dc.q) for dc in dcs]
+    d_len = torch.zeros(2, dtype=torch.int32, device="cuda")
+    d_acc = torch.zeros(2, case.max_depth + 1, dtype=torch.int32, device="cuda")
+    step = ver.bind_model_step([dc.q for dc in dcs], kvs, case.kv_len, case.node_offsets, d_par, d_tok, dcs[-1].logits,
+                               outs, d_len, d_acc)
+    step()
+    torch.cuda.synchronize()
+    assert ver.device_status() & 3 == 0
+    a_ref, res = O.verify(layers[-1])
+    assert d_len.cpu().tolist() == [r[0] for r in res]
+    for b, (L, path, toks) in enumerate(res):
+        assert d_acc[b, :L + 1].cpu().tolist() == toks.tolist()
+    for c, dc, out in zip(layers, dcs, outs):
+        got = W.to_f64(B.to_host(out, case.dtype), case.dtype)
+        check_attention(c, got, O.attention(c), "model step layer")
+        k_ref, v_ref = c.k.copy(), c.v.copy()
+        for b, (L, path, toks) in enumerate(res):
+            O.compact(c, k_ref, v_ref, b, path)
+        assert np.array_equal(B.to_host(dc.k, case.dtype), k_ref) and np.array_equal(B.to_host(dc.v, case.dtype), v_ref)
+    ver.close()
