@@ -16,6 +16,14 @@ forward that would produce q/k/v and the logits.  A stand-in target takes its pl
 Because verification is lossless (Section 2.2), the emitted tokens must equal the stream
 token for token whatever the drafter proposes; `run()` checks that after every step.
 
+Two ways of keeping the accepted tokens' K/V (`policy`):
+  * "compact": this library's -- cb_compact_kv moves the accepted nodes' K/V into place, the next
+    tree's only non-cached token is its root;
+  * "refeed": the paper's (Section 3.2: the tokens accepted in the last step are not KV-cached, they
+    are fed again and count towards the total draft length) -- no compaction; the next tree starts
+    with a chain of the tokens emitted last step, the draft subtree hangs under the chain's end, and
+    the chain's K/V lands in its final slots by itself.
+
     python -m paper_2511_21699_amd.decode_loop --steps 1000          # one JSON line
 """
 from __future__ import annotations
@@ -47,11 +55,12 @@ def target_outputs(stream: np.ndarray, pos_root: int, parent, token, depth, voca
 
 def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_cap: int = 6, prompt_len: int = 2048,
         Hq: int = 32, Hkv: int = 32, D: int = 128, vocab: int = 32000, ll: int = 2, fl: int = 3, lc: int = 8192,
-        fc: int = 4, seed: int = 7, device: str = "cuda:0", check_with=None, warmup: int = 50) -> dict:
+        fc: int = 4, seed: int = 7, device: str = "cuda:0", check_with=None, warmup: int = 50,
+        policy: str = "compact") -> dict:
     """Runs `warmup` untimed and then `steps` timed decode steps; returns timings and acceptance statistics.
 
-    ``check_with(step, parent, token, logits_rows_host, accepted_tokens)`` is an optional callback for
-    tests (called for the first steps with the step's logits copied to the host)."""
+    ``check_with(step, parent, token, logits_rows, accepted_tokens)`` is an optional callback for tests
+    (the step's tree, its logits rows on the device and everything the verification returned)."""
     import torch
     rng = np.random.default_rng(seed)
     room = (steps + warmup + 4) * (depth_cap + 1)
@@ -64,17 +73,25 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
     q = torch.randn(node_budget, Hq, D, generator=gen).to(torch.bfloat16).to(dev)
     base = (torch.rand(node_budget, vocab, generator=gen) * 2 - 1).to(torch.bfloat16).to(dev)
     logits = base.clone()
-    cfg = B.make_config(Hq, Hkv, D, "bf16", "bf16", 1, node_budget, depth_cap, vocab)
+    if policy not in ("compact", "refeed"):
+        raise ValueError("policy must be 'compact' or 'refeed'")
+    refeed = policy == "refeed"
+    # with re-feeding the tree is a chain of up to depth_cap + 1 emitted tokens with the draft subtree below it
+    cfg = B.make_config(Hq, Hkv, D, "bf16", "bf16", 1, node_budget, 2 * depth_cap + 1 if refeed else depth_cap, vocab)
     ver = B.Verifier(cfg, device=device)
     kv = B.kv_layer(k, v)
     if drafter == "native":
         table = B.DraftTable(ll, fl, lc, fc)
-        grower = B.TreeGrower([table], node_budget, depth_cap)
-        grow = lambda text, n: grower.grow(text, n)
+        growers = {}
+
+        def grow(text, n, budget=node_budget):
+            if budget not in growers:
+                growers[budget] = B.TreeGrower([table], budget, depth_cap)
+            return growers[budget].grow(text, n)
         update = lambda toks, start: table.update(toks, start)
     elif drafter == "python":
         table = PY.CacheTable(ll, fl, lc, fc)
-        grow = lambda text, n: PY.grow_tree(text[:n], [table], node_budget, depth_cap)
+        grow = lambda text, n, budget=node_budget: PY.grow_tree(text[:n], [table], budget, depth_cap)
         update = lambda toks, start: table.update_sliding_window(toks, start)
     else:
         raise ValueError("drafter must be 'native' or 'python'")
@@ -85,6 +102,7 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
     t_draft = t_target = t_verify = t_compact = t_update = 0.0
     accepted_total, nodes_total, text0 = 0, 0, prompt_len
     kv_len = np.asarray([n_text - 1], dtype=np.int32)               # the root token's K/V is not cached yet
+    pending = 1                                                     # tokens at the end of the text without cached K/V
     torch.cuda.synchronize(dev)
     wall0 = time.perf_counter()
     try:
@@ -95,32 +113,47 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
                 accepted_total, nodes_total, text0 = 0, 0, n_text
                 wall0 = time.perf_counter()
             t0 = time.perf_counter()
-            parent, token, depth = grow(emitted, n_text)
+            if refeed:
+                # chain of the `pending` non-cached tokens, then the draft subtree under its last node;
+                # the chain counts towards the budget (the paper's TDL counts non-cached tokens)
+                sp, stk, sd = grow(emitted, n_text, node_budget - (pending - 1))
+                c = pending - 1
+                parent = np.concatenate([np.arange(-1, c - 1, dtype=np.int32), np.asarray(sp, dtype=np.int32) + c])
+                parent[c] = c - 1
+                token = np.concatenate([emitted[n_text - pending:n_text - 1], np.asarray(stk, dtype=np.int32)])
+                depth = np.concatenate([np.arange(c, dtype=np.int32), np.asarray(sd, dtype=np.int32) + c])
+            else:
+                parent, token, depth = grow(emitted, n_text)
             t1 = time.perf_counter()
             parent = np.asarray(parent, dtype=np.int32)
             token = np.asarray(token, dtype=np.int32)
             n = len(parent)
+            root_pos = n_text - pending                              # text index of tree node 0
             # ---- stand-in for the model forward: logits rows for the tree's nodes
-            outs = target_outputs(stream, n_text - 1, parent, token, depth, vocab)
+            outs = target_outputs(stream, root_pos, parent, token, depth, vocab)
             logits[:n].copy_(base[:n])
             logits[torch.arange(n, device=dev), torch.from_numpy(outs).to(dev).long()] = 8.0
             torch.cuda.synchronize(dev)
             t2 = time.perf_counter()
-            kv_len[0] = n_text - 1
+            kv_len[0] = root_pos
             _, acc_len, acc_tok = ver.verify_tree(q[:n], kv, kv_len, [0, n], parent, token, logits[:n])
             t3 = time.perf_counter()
-            ver.compact_kv([kv], 1)
+            if not refeed:
+                ver.compact_kv([kv], 1)
             t4 = time.perf_counter()
-            L = int(acc_len[0])
-            new = acc_tok[0, :L + 1]
+            L = int(acc_len[0]) - (pending - 1)                      # newly accepted draft tokens
+            if L < 0:
+                raise AssertionError(f"step {step}: the re-fed chain itself was not accepted")
+            new = acc_tok[0, pending - 1:pending + L]
             if check_with is not None:
-                check_with(step + warmup, parent, token, logits[:n], new)
+                check_with(step + warmup, parent, token, logits[:n], acc_tok[0, :int(acc_len[0]) + 1])
             if not np.array_equal(new, stream[n_text:n_text + L + 1]):
                 raise AssertionError(f"step {step}: emitted {new.tolist()} but the text continues "
                                      f"{stream[n_text:n_text + L + 1].tolist()} (verification must be lossless)")
             emitted[n_text:n_text + L + 1] = new
             old = n_text
             n_text += L + 1
+            pending = L + 1 if refeed else 1
             t5 = time.perf_counter()
             update(emitted[:n_text], old - (fl - 1))               # every window that touches a new token
             t6 = time.perf_counter()
@@ -135,7 +168,7 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
             table.close()
     us = lambda t: round(t / steps * 1e6, 2)
     own = t_draft + t_verify + t_compact + t_update                 # everything except the stand-in target
-    return {"steps": steps, "drafter": drafter, "warmup": warmup, "tokens_emitted": int(n_text - text0),
+    return {"steps": steps, "drafter": drafter, "policy": policy, "warmup": warmup, "tokens_emitted": int(n_text - text0),
             "mean_accepted_tokens_per_step": round((n_text - text0) / steps, 3),
             "mean_tree_nodes": round(nodes_total / steps, 1),
             "draft_us": us(t_draft), "verify_us": us(t_verify), "compact_us": us(t_compact), "table_update_us": us(t_update),
@@ -152,10 +185,11 @@ def main():
     ap.add_argument("--drafter", default="native", choices=["native", "python"])
     ap.add_argument("--prompt", type=int, default=2048)
     ap.add_argument("--nodes", type=int, default=64)
+    ap.add_argument("--policy", default="compact", choices=["compact", "refeed"])
     ap.add_argument("--warmup", type=int, default=2000, help="untimed steps first (the GPU takes a few tenths of a second to settle)")
     args = ap.parse_args()
     print(json.dumps(run(steps=args.steps, drafter=args.drafter, prompt_len=args.prompt, node_budget=args.nodes,
-                         warmup=args.warmup)))
+                         warmup=args.warmup, policy=args.policy)))
 
 
 if __name__ == "__main__":

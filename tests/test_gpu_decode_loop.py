@@ -9,8 +9,8 @@ from paper_2511_21699_amd import decode_loop
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("drafter", ["native", "python"])
-def test_decode_loop_is_lossless_and_agrees_with_the_oracle_step_by_step(drafter):
+@pytest.mark.parametrize("drafter,policy", [("native", "compact"), ("python", "compact"), ("native", "refeed")])
+def test_decode_loop_is_lossless_and_agrees_with_the_oracle_step_by_step(drafter, policy):
     from oracle import cb_oracle as O
     checked = []
 
@@ -24,7 +24,7 @@ def test_decode_loop_is_lossless_and_agrees_with_the_oracle_step_by_step(drafter
 
     # run() itself raises if an emitted token differs from the text (lossless decoding)
     r = decode_loop.run(steps=150, drafter=drafter, node_budget=48, depth_cap=6, prompt_len=700, Hq=8, Hkv=8,
-                        vocab=5000, lc=4096, seed=11, check_with=check, warmup=0)
+                        vocab=5000, lc=4096, seed=11, check_with=check, warmup=0, policy=policy)
     assert len(checked) == 25 and r["lossless"]
     assert r["tokens_emitted"] >= 150                      # at least the bonus token every step
     assert r["mean_accepted_tokens_per_step"] > 1.2        # the copied spans of the text make drafts hit
@@ -35,3 +35,12 @@ def test_native_and_python_drafters_drive_identical_decodes():
     a = decode_loop.run(steps=60, drafter="native", node_budget=32, prompt_len=500, Hq=4, Hkv=4, vocab=3000, seed=5, warmup=3)
     b = decode_loop.run(steps=60, drafter="python", node_budget=32, prompt_len=500, Hq=4, Hkv=4, vocab=3000, seed=5, warmup=3)
     assert a["tokens_emitted"] == b["tokens_emitted"] and a["mean_tree_nodes"] == b["mean_tree_nodes"]
+
+
+def test_refeeding_and_compaction_emit_the_same_text():
+    """The paper's policy (accepted tokens fed again, Section 3.2) and this library's (their K/V compacted in
+    place) are two ways to the same text; re-feeding spends part of the draft budget on the chain."""
+    a = decode_loop.run(steps=80, policy="compact", node_budget=24, prompt_len=400, Hq=4, Hkv=4, vocab=2000, seed=9, warmup=0)
+    b = decode_loop.run(steps=80, policy="refeed", node_budget=24, prompt_len=400, Hq=4, Hkv=4, vocab=2000, seed=9, warmup=0)
+    assert a["lossless"] and b["lossless"]
+    assert b["tokens_emitted"] <= a["tokens_emitted"] * 1.05 + 5
