@@ -11,7 +11,6 @@ constexpr int kArgmaxChunk = 8192;            // logits elements scanned by one 
 constexpr int kRowTile = 64;                  // query rows per workgroup in the MFMA attention
 // floats per (row, split) partial softmax state: o[D] unnormalised, m, l, padded to 16 bytes
 constexpr int partial_stride(int D) { return D + 4; }
-constexpr int kPartialStrideD128 = partial_stride(128);
 
 // Per-sequence shapes; passed to kernels by value (kernel arguments), so they need no upload and
 // are captured with the launch.

@@ -100,7 +100,7 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
     n_text = prompt_len
     update(emitted[:n_text], 0)                                     # prompt initialisation (Section 3.3)
     t_draft = t_target = t_verify = t_compact = t_update = 0.0
-    accepted_total, nodes_total, text0 = 0, 0, prompt_len
+    nodes_total, text0 = 0, prompt_len
     kv_len = np.asarray([n_text - 1], dtype=np.int32)               # the root token's K/V is not cached yet
     pending = 1                                                     # tokens at the end of the text without cached K/V
     torch.cuda.synchronize(dev)
@@ -110,7 +110,7 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
             if step == 0:                                           # the timed part starts here
                 torch.cuda.synchronize(dev)
                 t_draft = t_target = t_verify = t_compact = t_update = 0.0
-                accepted_total, nodes_total, text0 = 0, 0, n_text
+                nodes_total, text0 = 0, n_text
                 wall0 = time.perf_counter()
             t0 = time.perf_counter()
             if refeed:
@@ -158,7 +158,6 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
             update(emitted[:n_text], old - (fl - 1))               # every window that touches a new token
             t6 = time.perf_counter()
             t_draft += t1 - t0; t_target += t2 - t1; t_verify += t3 - t2; t_compact += t4 - t3; t_update += t6 - t5
-            accepted_total += L
             nodes_total += n
         torch.cuda.synchronize(dev)
         wall = time.perf_counter() - wall0
