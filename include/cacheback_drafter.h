@@ -5,7 +5,8 @@
  * table of leader -> follower n-grams with LRU eviction in both domains (Section 3.1), and the
  * breadth-first growth of the draft-token tree by recursive table queries (Section 3.2).  Its
  * trees are the input of cb_verify_tree (cacheback.h).  Nothing here touches a GPU; every pointer
- * is host memory; no function allocates after cbd_table_create except the table's hash index.
+ * is host memory; after cbd_table_create only the table's hash index allocates (and
+ * cbd_table_build_frozen, which counts n-grams in temporary maps).
  *
  * Readings where the paper is silent (they shape the trees, never the verified results):
  * a query returns followers most-recently-inserted first; re-inserting a follower that is present
@@ -50,6 +51,14 @@ int cbd_table_query(cbd_table *t, const int32_t *leader, int32_t refresh, int32_
 
 /* Section 3.3: a frozen table keeps answering queries but ignores insertions and recency. */
 int cbd_table_freeze(cbd_table *t);
+
+/* Section 4 (how the paper builds its frozen table from a corpus sample): over all windows
+ * (tokens[i-ll .. i), tokens[i .. i+fl)), i in [ll, n - fl], the `lc` most frequent leaders are
+ * kept, and for each of them its `fc` most frequent followers; among equally frequent n-grams the
+ * one whose first window comes earlier in the sample wins.  The new table is frozen; a query returns
+ * a leader's followers most frequent first. */
+int cbd_table_build_frozen(int32_t ll, int32_t fl, int32_t lc, int32_t fc, const int32_t *tokens, int64_t n,
+                           cbd_table **out);
 
 /* Current numbers of leaders and of followers (over all leaders). */
 int cbd_table_size(const cbd_table *t, int64_t *leaders, int64_t *followers);

@@ -1,8 +1,8 @@
 """Oracle of the host drafter: TEST INFRASTRUCTURE ONLY (imported by tests/ and by nothing else).
 
 A plain, slow, obviously correct model of Cacheback's cache table and draft-tree growth, written
-from the paper with Python lists and linear scans only -- no hash maps, no ordered dictionaries, no
-code shared with the product's drafters (paper_2511_21699_amd/drafter.py, csrc/cb_drafter.cpp).
+from the paper with Python lists, linear scans and sorting only -- no hash maps, no ordered dictionaries,
+no code shared with the product's drafters (paper_2511_21699_amd/drafter.py, csrc/cb_drafter.cpp).
 
 Section 3.1 (the cache table): pairs of a leader (LL tokens) and its followers (FL tokens each);
 at most LC leaders and FC followers per leader; both domains evict their least recently used
@@ -123,3 +123,35 @@ def grow_tree_oracle(context, tables, node_budget, depth_cap, crt=0):
                         reached.append(at)
             frontier = [n for n in reached if not kids(n)]
     return parent, token, depth
+
+
+def build_frozen_oracle(tokens, ll, fl, lc, fc):
+    """Section 4: the frozen table from a corpus sample -- the LC most frequent leaders (LL-grams) and,
+    per leader, its FC most frequent followers (FL-grams that come right after it).  Counted over the
+    windows (leader, follower) that fit in the sample; equal counts: the earlier first window wins.
+    Counting is done by sorting the windows and measuring runs."""
+    tokens = [int(x) for x in tokens]
+    wins = []                                          # (leader, follower, position)
+    for i in range(ll, len(tokens) - fl + 1):
+        wins.append((tuple(tokens[i - ll:i]), tuple(tokens[i:i + fl]), i))
+
+    def runs(items):                                   # items: (key, position) -> [(count, first position, key)]
+        items = sorted(items)
+        out = []
+        for key, pos in items:
+            if out and out[-1][2] == key:
+                out[-1][0] += 1
+            else:
+                out.append([1, pos, key])
+        return out
+
+    leaders = runs([(w[0], w[2]) for w in wins])
+    leaders.sort(key=lambda r: (-r[0], r[1]))
+    t = TableOracle(ll, fl, lc, fc)
+    for _, _, leader in reversed(leaders[:lc]):
+        fols = runs([(w[1], w[2]) for w in wins if w[0] == leader])
+        fols.sort(key=lambda r: (-r[0], r[1]))
+        for _, _, fol in reversed(fols[:fc]):
+            t.insert(leader, fol)
+    t.frozen = True
+    return t

@@ -26,7 +26,7 @@ EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_att
 
 
 DRAFTER_EXPORTS = ["cbd_table_create", "cbd_table_destroy", "cbd_table_insert", "cbd_table_update", "cbd_table_query",
-                   "cbd_table_freeze", "cbd_table_size", "cbd_grow_tree"]
+                   "cbd_table_build_frozen", "cbd_table_freeze", "cbd_table_size", "cbd_grow_tree"]
 
 
 class CbConfig(C.Structure):
@@ -81,6 +81,7 @@ def load():
     L.cbd_table_insert.argtypes = [vp, i32p, i32p]
     L.cbd_table_update.argtypes = [vp, i32p, C.c_int64, C.c_int64]
     L.cbd_table_query.argtypes = [vp, i32p, C.c_int32, i32p, i32p]
+    L.cbd_table_build_frozen.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p, C.c_int64, C.POINTER(vp)]
     L.cbd_table_freeze.argtypes = [vp]
     L.cbd_table_size.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     L.cbd_grow_tree.argtypes = [C.POINTER(vp), C.c_int32, i32p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
@@ -313,11 +314,16 @@ class Verifier:
 class DraftTable:
     """One leader -> follower cache table of the native drafter."""
 
-    def __init__(self, ll: int, fl: int, lc: int, fc: int):
+    def __init__(self, ll: int, fl: int, lc: int, fc: int, frozen_from=None):
+        """An empty table, or (``frozen_from`` = token sample) the frozen table built from a corpus sample."""
         self.L = load()
         self.ll, self.fl, self.lc, self.fc = ll, fl, lc, fc
         h = C.c_void_p()
-        rc = self.L.cbd_table_create(ll, fl, lc, fc, C.byref(h))
+        if frozen_from is None:
+            rc = self.L.cbd_table_create(ll, fl, lc, fc, C.byref(h))
+        else:
+            a = _i32(frozen_from)
+            rc = self.L.cbd_table_build_frozen(ll, fl, lc, fc, _ip(a), len(a), C.byref(h))
         if rc:
             raise CbError(rc, "cbd_table_create")
         self.h = h

@@ -211,6 +211,46 @@ int cbd_table_query(cbd_table* t, const int32_t* leader, int32_t refresh, int32_
   return CB_OK;
 }
 
+int cbd_table_build_frozen(int32_t ll, int32_t fl, int32_t lc, int32_t fc, const int32_t* tokens, int64_t n,
+                           cbd_table** out) {
+  if (!out || (!tokens && n > 0) || n < 0) return CB_EINVAL;
+  cbd_table* t = nullptr;
+  const int rc = cbd_table_create(ll, fl, lc, fc, &t);
+  if (rc) return rc;
+  struct Stat {
+    int64_t count = 0, first = 0;
+    std::unordered_map<KeyRef, std::pair<int64_t, int64_t>, KeyHash, KeyEq> followers;  // -> (count, first window)
+  };
+  std::unordered_map<KeyRef, Stat, KeyHash, KeyEq> leaders;  // keys point into `tokens`
+  for (int64_t i = ll; i + fl <= n; i++) {
+    Stat& st = leaders[KeyRef{tokens + i - ll, ll}];
+    if (st.count++ == 0) st.first = i;
+    auto& f = st.followers[KeyRef{tokens + i, fl}];
+    if (f.first++ == 0) f.second = i;
+  }
+  // more frequent first, then earlier first window
+  std::vector<std::pair<KeyRef, const Stat*>> top;
+  top.reserve(leaders.size());
+  for (const auto& kv : leaders) top.emplace_back(kv.first, &kv.second);
+  std::sort(top.begin(), top.end(), [](const auto& a, const auto& b) {
+    return a.second->count != b.second->count ? a.second->count > b.second->count : a.second->first < b.second->first;
+  });
+  if ((int64_t)top.size() > lc) top.resize((size_t)lc);
+  std::vector<std::pair<KeyRef, std::pair<int64_t, int64_t>>> fols;
+  for (size_t r = top.size(); r-- > 0;) {  // least frequent leader first (recency is irrelevant once frozen)
+    fols.assign(top[r].second->followers.begin(), top[r].second->followers.end());
+    std::sort(fols.begin(), fols.end(), [](const auto& a, const auto& b) {
+      return a.second.first != b.second.first ? a.second.first > b.second.first : a.second.second < b.second.second;
+    });
+    if ((int64_t)fols.size() > fc) fols.resize((size_t)fc);
+    for (size_t k = fols.size(); k-- > 0;)  // least frequent follower first: the most frequent ends up most recent
+      cbd_table_insert(t, top[r].first.p, fols[k].first.p);
+  }
+  t->frozen = true;
+  *out = t;
+  return CB_OK;
+}
+
 int cbd_table_freeze(cbd_table* t) {
   if (!t) return CB_EINVAL;
   t->frozen = true;

@@ -56,15 +56,29 @@ def target_outputs(stream: np.ndarray, pos_root: int, parent, token, depth, voca
 def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_cap: int = 6, prompt_len: int = 2048,
         Hq: int = 32, Hkv: int = 32, D: int = 128, vocab: int = 32000, ll: int = 2, fl: int = 3, lc: int = 8192,
         fc: int = 4, seed: int = 7, device: str = "cuda:0", check_with=None, warmup: int = 50,
-        policy: str = "compact") -> dict:
+        policy: str = "compact", tables: str = "dynamic", corpus_tokens: int = 200000, use_only: str = "") -> dict:
     """Runs `warmup` untimed and then `steps` timed decode steps; returns timings and acceptance statistics.
 
+    ``tables``: "dynamic" drafts from the dynamic table on the benchmark's stream; "dual" and "frozen" use a
+    text with a shared phrase book and a frozen table built from a corpus sample of ``corpus_tokens`` tokens
+    (Sections 3.3 and 4); ``use_only="dynamic"`` with ``tables="dual"`` is the same text without the frozen
+    table (the "No Frozen" row of the paper's Table 1).
     ``check_with(step, parent, token, logits_rows, accepted_tokens)`` is an optional callback for tests
     (the step's tree, its logits rows on the device and everything the verification returned)."""
     import torch
     rng = np.random.default_rng(seed)
     room = (steps + warmup + 4) * (depth_cap + 1)
-    stream = W.zipf_stream(rng, prompt_len + room + 64, vocab)
+    if tables not in ("dynamic", "dual", "frozen"):
+        raise ValueError("tables must be 'dynamic', 'dual' or 'frozen'")
+    if tables == "dynamic":
+        stream = W.zipf_stream(rng, prompt_len + room + 64, vocab)
+        corpus = None
+    else:
+        # a "language" (phrase book), a corpus sample written in it for the frozen table (Section 4)
+        # and, independently, the text to decode
+        book = W.phrase_book(rng, 4000, vocab)
+        corpus = W.phrase_stream(rng, corpus_tokens, vocab, book)
+        stream = W.phrase_stream(rng, prompt_len + room + 64, vocab, book)
     gen = torch.Generator(device="cpu").manual_seed(seed)
     cap = prompt_len + room + node_budget
     dev = torch.device(device)
@@ -80,16 +94,22 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
     cfg = B.make_config(Hq, Hkv, D, "bf16", "bf16", 1, node_budget, 2 * depth_cap + 1 if refeed else depth_cap, vocab)
     ver = B.Verifier(cfg, device=device)
     kv = B.kv_layer(k, v)
+    frozen = None
     if drafter == "native":
         table = B.DraftTable(ll, fl, lc, fc)
+        if corpus is not None:
+            frozen = B.DraftTable(ll, fl, lc, fc, frozen_from=corpus)
+        use = {"dynamic": [table], "dual": [table, frozen], "frozen": [frozen]}[use_only or tables]   # dynamic first (Section 3.3)
         growers = {}
 
         def grow(text, n, budget=node_budget):
             if budget not in growers:
-                growers[budget] = B.TreeGrower([table], budget, depth_cap)
+                growers[budget] = B.TreeGrower(use, budget, depth_cap)
             return growers[budget].grow(text, n)
         update = lambda toks, start: table.update(toks, start)
     elif drafter == "python":
+        if tables != "dynamic":
+            raise ValueError("the frozen-table configurations use the native drafter")
         table = PY.CacheTable(ll, fl, lc, fc)
         grow = lambda text, n, budget=node_budget: PY.grow_tree(text[:n], [table], budget, depth_cap)
         update = lambda toks, start: table.update_sliding_window(toks, start)
@@ -165,9 +185,11 @@ def run(steps: int = 200, drafter: str = "native", node_budget: int = 64, depth_
         ver.close()
         if drafter == "native":
             table.close()
+            if frozen is not None:
+                frozen.close()
     us = lambda t: round(t / steps * 1e6, 2)
     own = t_draft + t_verify + t_compact + t_update                 # everything except the stand-in target
-    return {"steps": steps, "drafter": drafter, "policy": policy, "warmup": warmup, "tokens_emitted": int(n_text - text0),
+    return {"steps": steps, "drafter": drafter, "policy": policy, "tables": tables, "warmup": warmup, "tokens_emitted": int(n_text - text0),
             "mean_accepted_tokens_per_step": round((n_text - text0) / steps, 3),
             "mean_tree_nodes": round(nodes_total / steps, 1),
             "draft_us": us(t_draft), "verify_us": us(t_verify), "compact_us": us(t_compact), "table_update_us": us(t_update),
@@ -185,10 +207,22 @@ def main():
     ap.add_argument("--prompt", type=int, default=2048)
     ap.add_argument("--nodes", type=int, default=64)
     ap.add_argument("--policy", default="compact", choices=["compact", "refeed"])
+    ap.add_argument("--tables", default="dynamic", choices=["dynamic", "dual", "frozen"],
+                    help="dynamic table only (on the benchmark's stream), or the paper's table configurations on a "
+                         "text with a shared phrase book: dual (dynamic then frozen), frozen only")
+    ap.add_argument("--ablate", action="store_true", help="the three table configurations of the paper's Table 1 on one text")
     ap.add_argument("--warmup", type=int, default=2000, help="untimed steps first (the GPU takes a few tenths of a second to settle)")
     args = ap.parse_args()
+    if args.ablate:
+        for name, kw in (("Dual", dict(tables="dual")), ("No Frozen", dict(tables="dual", use_only="dynamic")),
+                         ("Only Frozen", dict(tables="frozen"))):
+            r = run(steps=args.steps, prompt_len=args.prompt, node_budget=args.nodes, warmup=min(args.warmup, 200), **kw)
+            print(json.dumps({"configuration": name, "mean_accepted_tokens_per_step": r["mean_accepted_tokens_per_step"],
+                              "mean_tree_nodes": r["mean_tree_nodes"], "draft_us": r["draft_us"],
+                              "steps_per_s_without_target": r["steps_per_s_without_target"]}))
+        return
     print(json.dumps(run(steps=args.steps, drafter=args.drafter, prompt_len=args.prompt, node_budget=args.nodes,
-                         warmup=args.warmup, policy=args.policy)))
+                         warmup=args.warmup, policy=args.policy, tables=args.tables)))
 
 
 if __name__ == "__main__":

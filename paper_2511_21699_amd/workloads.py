@@ -203,6 +203,46 @@ def zipf_stream(rng: np.random.Generator, length: int, vocab: int, exponent: flo
     return out[:length].copy()
 
 
+def phrase_book(rng: np.random.Generator, phrases: int, vocab: int, span: Tuple[int, int] = (3, 8),
+                exponent: float = 1.1) -> list:
+    """A fixed list of token phrases (lengths uniform in ``span``, tokens truncated-Zipf): the part of
+    a synthetic "language" that every text written in it shares."""
+    w = np.arange(1, vocab + 1, dtype=np.float64) ** (-exponent)
+    cdf = np.cumsum(w) / w.sum()
+    return [np.minimum(np.searchsorted(cdf, rng.random(int(rng.integers(span[0], span[1] + 1)))), vocab - 1).astype(np.int32)
+            for _ in range(phrases)]
+
+
+def phrase_stream(rng: np.random.Generator, length: int, vocab: int, book: list, p_phrase: float = 0.45,
+                  p_repeat: float = 0.2, span: Tuple[int, int] = (4, 16), exponent: float = 1.1) -> np.ndarray:
+    """Text in the "language" of ``book``: at each decision point a phrase of the book (Zipf-weighted
+    choice) with probability ``p_phrase``, a copy of an earlier span of this text with probability
+    ``p_repeat``, else one truncated-Zipf token.  Two texts over the same book share their phrases
+    (what a table built offline from a corpus can know) but not their own repetitions (what only a
+    table updated while decoding can know)."""
+    w = np.arange(1, vocab + 1, dtype=np.float64) ** (-exponent)
+    cdf = np.cumsum(w) / w.sum()
+    bw = np.arange(1, len(book) + 1, dtype=np.float64) ** (-exponent)
+    bcdf = np.cumsum(bw) / bw.sum()
+    out = np.empty(length + 64, dtype=np.int32)
+    t = 0
+    while t < length:
+        u = rng.random()
+        if u < p_phrase:
+            ph = book[min(int(np.searchsorted(bcdf, rng.random())), len(book) - 1)]
+            out[t:t + len(ph)] = ph
+            t += len(ph)
+        elif u < p_phrase + p_repeat and t >= span[0]:
+            ln = min(int(rng.integers(span[0], span[1] + 1)), t)
+            s0 = int(rng.integers(0, t - ln + 1))
+            out[t:t + ln] = out[s0:s0 + ln]
+            t += ln
+        else:
+            out[t] = min(int(np.searchsorted(cdf, rng.random())), vocab - 1)
+            t += 1
+    return out[:length].copy()
+
+
 def drafter_tree(rng: np.random.Generator, n_nodes: int, depth_cap: int, vocab: int = 32000,
                  stream_len: int = 32768, ll: int = 2, fl: int = 3, fc: int = 4, lc: int = 8192,
                  max_children: int = 4) -> Tuple[np.ndarray, np.ndarray, Dict]:

@@ -9,7 +9,7 @@ import re
 import numpy as np
 import pytest
 
-from oracle.drafter_oracle import TableOracle, grow_tree_oracle
+from oracle.drafter_oracle import TableOracle, build_frozen_oracle, grow_tree_oracle
 from paper_2511_21699_amd import binding as B
 from paper_2511_21699_amd import drafter as P
 from paper_2511_21699_amd import workloads as W
@@ -185,3 +185,32 @@ def test_drafter_header_symbols_are_exported_and_bad_arguments_are_refused():
     assert L.cbd_grow_tree((C.c_void_p * 1)(t.h), 1, B._ip(one), 0, 4, 4, 0, B._ip(one), B._ip(one), B._ip(one), C.byref(n)) == B.CB_EINVAL
     assert L.cbd_grow_tree((C.c_void_p * 1)(t.h), 1, B._ip(one), 1, 0, 4, 0, B._ip(one), B._ip(one), B._ip(one), C.byref(n)) == B.CB_EINVAL
     t.close()
+
+
+def test_frozen_table_build_oracle_hand_counted():
+    """Section 4: most frequent leaders, then each leader's most frequent followers (hand-counted sample)."""
+    #        windows (LL = 1, FL = 1):  1>2 2>1 1>2 2>3 3>1 1>3 3>1 1>2   -> leader 1 x4, 2 x2, 3 x2
+    toks = [1, 2, 1, 2, 3, 1, 3, 1, 2]
+    t = build_frozen_oracle(toks, 1, 1, 2, 1)
+    assert t.size() == (2, 2)                              # leaders 1 and 2 (2 and 3 tie at two; 2 came first)
+    assert t.query([1], refresh=False) == [(2,)]           # after 1: 2 x3, 3 x1
+    assert t.query([2], refresh=False) == [(1,)]           # after 2: 1 and 3 once each; 1 came first
+    assert t.query([3], refresh=False) == []
+    t.insert([9], [9])
+    assert t.size() == (2, 2)                              # frozen
+    t2 = build_frozen_oracle(toks, 1, 1, 8, 8)
+    assert t2.query([1], refresh=False) == [(2,), (3,)] and t2.query([3], refresh=False) == [(1,)]
+
+
+@pytest.mark.parametrize("seed,ll,fl,lc,fc,vocab", [(0, 2, 3, 50, 3, 12), (1, 1, 1, 5, 2, 6), (2, 3, 2, 1000, 4, 40)])
+def test_native_frozen_table_build_matches_the_oracle(seed, ll, fl, lc, fc, vocab):
+    rng = np.random.default_rng(300 + seed)
+    toks = W.zipf_stream(rng, 3000, vocab)
+    o = build_frozen_oracle(toks, ll, fl, lc, fc)
+    n = B.DraftTable(ll, fl, lc, fc, frozen_from=toks)
+    assert n.size() == o.size()
+    for row in o.rows:
+        assert n.query(row[0], refresh=False) == o.query(row[0], refresh=False)
+    n.insert([0] * ll, [1] * fl)
+    assert n.size() == o.size()
+    n.close()

@@ -44,3 +44,18 @@ def test_refeeding_and_compaction_emit_the_same_text():
     b = decode_loop.run(steps=80, policy="refeed", node_budget=24, prompt_len=400, Hq=4, Hkv=4, vocab=2000, seed=9, warmup=0)
     assert a["lossless"] and b["lossless"]
     assert b["tokens_emitted"] <= a["tokens_emitted"] * 1.05 + 5
+
+
+def test_dual_tables_beat_either_table_alone_on_a_text_with_shared_phrases():
+    """Section 3.3 / Table 1 of the paper, on a synthetic language: the frozen table (built from a corpus
+    sample, Section 4) knows the shared phrases, the dynamic one the text's own repetitions; drafting from
+    both accepts more tokens per step than drafting from either."""
+    kw = dict(steps=250, node_budget=48, prompt_len=600, Hq=4, Hkv=4, vocab=8000, lc=4096, seed=13, warmup=0,
+              corpus_tokens=60000)
+    dual = decode_loop.run(tables="dual", **kw)
+    dyn = decode_loop.run(tables="dual", use_only="dynamic", **kw)
+    frz = decode_loop.run(tables="frozen", **kw)
+    assert dual["lossless"] and dyn["lossless"] and frz["lossless"]
+    assert dual["mean_accepted_tokens_per_step"] > dyn["mean_accepted_tokens_per_step"] + 0.1
+    assert dual["mean_accepted_tokens_per_step"] > frz["mean_accepted_tokens_per_step"] + 0.1
+    assert dual["mean_tree_nodes"] > dyn["mean_tree_nodes"]            # the frozen table grows the tree further
