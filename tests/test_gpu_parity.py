@@ -353,3 +353,26 @@ def test_model_step_of_several_layers(kind):
             O.compact(c, k_ref, v_ref, b, path)
         assert np.array_equal(B.to_host(dc.k, case.dtype), k_ref) and np.array_equal(B.to_host(dc.v, case.dtype), v_ref)
     ver.close()
+
+
+@pytest.mark.parametrize("qkv,lg", [("bf16", "f32"), ("f32", "bf16")])
+def test_logits_dtype_independent_of_the_cache_dtype(qkv, lg):
+    """The configuration names the two element types separately; acceptance must be bit-exact for either mix."""
+    import torch
+    from oracle import cb_oracle as O
+    rng = np.random.default_rng(31)
+    par = W.random_tree(rng, 50, 4, 6, False)[0]
+    case = W.custom_case(141, qkv, 1, 8, 8, 128, 9001, [800], [par], p_match=0.8)
+    other = W.custom_case(142, lg, 1, 8, 8, 128, 9001, [800], [par], p_match=0.8)      # logits and tokens of the other type
+    dc = B.DeviceCase(case)
+    d_logits = B.to_device(other.logits, lg)
+    cfg = B.make_config(8, 8, 128, qkv, lg, 1, 50, case.max_depth, 9001)
+    ver = B.Verifier(cfg)
+    out, acc_len, acc_tok = ver.verify_tree(dc.q, dc.kv, case.kv_len, case.node_offsets, case.parent, other.tokens, d_logits)
+    torch.cuda.synchronize()
+    a = O.argmax(other.logits, lg)
+    assert np.array_equal(ver.get_argmax(50), a)
+    L, path, toks = O.accept(case.parent, other.tokens, a)
+    assert acc_len[0] == L and acc_tok[0, :L + 1].tolist() == toks.tolist() and L >= 1
+    check_attention(case, W.to_f64(B.to_host(out, qkv), qkv), O.attention(case), f"qkv {qkv} logits {lg}")
+    ver.close()
