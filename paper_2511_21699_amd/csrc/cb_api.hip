@@ -77,7 +77,8 @@ WsLayout ws_layout(const cb_config& c) {
   // argmax partials of the one-launch verification, one 128-byte line each (it takes sequences of at most 64 nodes)
   L.amax_lines = take((size_t)c.max_batch * std::min(c.max_nodes, 64) * L.amax_chunks * 128);
   L.dbg = take(1024 * 8 * 8);
-  L.partial = take(mt * c.num_q_heads * (size_t)L.max_splits * partial_stride(c.head_dim) * 4);
+  L.partial = take(std::max(mt * c.num_q_heads * (size_t)L.max_splits * partial_stride(c.head_dim) * 4,
+                            attn_mfma_partial_bytes(mt, c.num_q_heads, c.num_kv_heads, c.max_batch, L.max_splits)));
   L.total = o;
   return L;
 }

@@ -39,10 +39,21 @@ constexpr int kStageKeys = 32;                 // keys per LDS stage and wave gr
 constexpr int kStageVecs = kStageKeys * 16;    // 16-byte pieces per K (or V) stage: 32 rows x 256 B
 constexpr int NS = 4;                          // ring depth: NS-1 stages in flight
 constexpr int kMaxBtLds = 1024;                // block-table entries staged in LDS per split
-// Partial softmax state of one (row, split) in this kernel's own format: o[128] as bf16 (unnormalised,
-// relative to the reference weight), then m and l as fp32, padded to 16 bytes.  Halving the bytes
+// Partial softmax state in this kernel's own format, one unit per (16-row tile, split), laid out in
+// the order the MFMA accumulators hold it: for each of the 8 dim tiles dt, lane (kg, c) of the wave
+// that owns the 16 rows has 8 bytes -- o[row c][16 dt + 4 kg + {0..3}] as bf16, unnormalised, relative
+// to the reference weight -- at dt * 512 + lane * 8, so that a wave's store or load of one dim tile is
+// 512 contiguous bytes; then (m, l) as fp32 for each of the 16 rows.  bf16 halves the bytes, which
 // matters because one workgroup pulls all partials of its tile through a single compute unit.
-constexpr int kPartialBytes = 128 * 2 + 16;
+// The units of sequence b start at tile unit_tile0(b); kv head hk's row tile ti (16 rows) is unit
+// (hk * ceil(M_b / 16) + ti) * nsplit + split behind it.
+constexpr int kUnitMl = 8 * 512;
+constexpr int kUnitBytes = kUnitMl + 16 * 8;
+// first 16-row tile of a sequence whose nodes start at `off`: room for ceil(M_b / 16) tiles per kv
+// head without a prefix sum over the sequences' tile counts
+__host__ __device__ __forceinline__ int64_t unit_tile0(int64_t off, int Hq, int Hkv, int b) {
+  return ((off * Hq) >> 4) + (int64_t)(Hkv + 1) * b;
+}
 
 
 template <int N>
@@ -383,40 +394,36 @@ __device__ __forceinline__ void pin_logits_args(LogitsWork& w) {
 }
 #undef CB_PIN
 
-// Split merge for the rows of one tile by all NT threads of the workgroup: thread -> (row, slice
-// of DPT dims).  Partials are combined online, BS splits per batch with all of a batch's loads in
-// flight together: m = max m_t, w_t = e^(m_t - m), o = sum w_t o_t / sum w_t l_t.
-// POL is the buffer cache policy of the loads.
-template <int RT, int G, int POL>
-__device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_rsrc_t prsrc, int64_t seq_row0,
-                                           int row0, int M, int g, int off, int hk, int nsplit_b, int tid) {
+// Split merge of one tile by the waves that swept it: every lane merges the elements it held --
+// its query row, dims 16 dt + 4 kg + {0..3} of NDT dim tiles from dt0 -- which is also how the
+// partials are laid out, so each load of a wave is 512 contiguous bytes (ubyte[rr]: byte offset of
+// split 0's unit of the lane's rr-th row tile).  Splits are combined online, BS per batch with all
+// of a batch's loads in flight together: m = max m_t, w_t = e^(m_t - m),
+// o = sum w_t o_t / sum w_t l_t.  POL is the buffer cache policy of the loads.
+template <int R, int NDT, int POL>
+__device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const int64_t* grow, const uint32_t* ubyte,
+                                           CB_GLOBAL uint16_t* gout, int nsplit_b, int dt0, int l) {
   constexpr int D = 128;
-  constexpr int SL = 4 * G;        // slices per row
-  constexpr int DPT = D / SL;      // dims per thread
-  constexpr int VPT = DPT / 8;     // 16-byte loads (8 bf16) per split and thread
-  constexpr int BS = 16 / VPT;     // splits per batch
-  const int slice = tid % SL;
-  for (int rl = tid / SL; rl < RT; rl += 64) {
-    const int row = row0 + rl;
-    if (row >= M) break;
-    const int node = row / g, hg = row - node * g;
-    const int64_t gr = (int64_t)(off + node) * p.Hq + hk * g + hg;
-    const uint32_t rbyte = (uint32_t)((gr - seq_row0) * p.nsplit * kPartialBytes);
-    float acc[DPT];
+  constexpr int BS = 32 / NDT;  // splits per batch
+  const int kg = l >> 4, c = l & 15;
 #pragma unroll
-    for (int i = 0; i < DPT; i++) acc[i] = 0.f;
+  for (int rr = 0; rr < R; rr++) {
+    if (grow[rr] < 0) continue;
+    floatx4 acc[NDT];
+#pragma unroll
+    for (int i = 0; i < NDT; i++) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
     float lsum = 0.f, m_run = -INFINITY;
     for (int t0 = 0; t0 < nsplit_b; t0 += BS) {
-      uintx4 v[BS][VPT];
+      uintx2 v[BS][NDT];
       uintx2 ml[BS];
 #pragma unroll
       for (int u = 0; u < BS; u++) {
         const int t = (t0 + u < nsplit_b) ? t0 + u : nsplit_b - 1;
-        const uint32_t tb = rbyte + t * kPartialBytes;
-        ml[u] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + D * 2, 0, POL);
+        const uint32_t tb = ubyte[rr] + t * kUnitBytes;
+        ml[u] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + kUnitMl + c * 8, 0, POL);
 #pragma unroll
-        for (int i = 0; i < VPT; i++)
-          v[u][i] = __builtin_amdgcn_raw_buffer_load_b128(prsrc, tb + (slice * DPT + 8 * i) * 2, 0, POL);
+        for (int i = 0; i < NDT; i++)
+          v[u][i] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + (dt0 + i) * 512 + l * 8, 0, POL);
       }
       float mb = -INFINITY;
 #pragma unroll
@@ -425,7 +432,7 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_
       const float m_new = fmaxf(m_run, mb);
       const float resc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
 #pragma unroll
-      for (int i = 0; i < DPT; i++) acc[i] *= resc;
+      for (int i = 0; i < NDT; i++) acc[i] *= resc;
       lsum *= resc;
       m_run = m_new;
 #pragma unroll
@@ -434,24 +441,22 @@ __device__ __forceinline__ void merge_rows(const AttnParams& p, __amdgpu_buffer_
         const float wgt = (t0 + u < nsplit_b && mt != -INFINITY) ? __expf(mt - m_new) : 0.f;
         lsum = fmaf(__uint_as_float(ml[u][1]), wgt, lsum);
 #pragma unroll
-        for (int i = 0; i < VPT; i++)
-#pragma unroll
-          for (int k = 0; k < 4; k++) {
-            acc[8 * i + 2 * k] = fmaf(__uint_as_float(v[u][i][k] << 16), wgt, acc[8 * i + 2 * k]);
-            acc[8 * i + 2 * k + 1] = fmaf(__uint_as_float(v[u][i][k] & 0xffff0000u), wgt, acc[8 * i + 2 * k + 1]);
-          }
+        for (int i = 0; i < NDT; i++) {
+          acc[i][0] = fmaf(__uint_as_float(v[u][i][0] << 16), wgt, acc[i][0]);
+          acc[i][1] = fmaf(__uint_as_float(v[u][i][0] & 0xffff0000u), wgt, acc[i][1]);
+          acc[i][2] = fmaf(__uint_as_float(v[u][i][1] << 16), wgt, acc[i][2]);
+          acc[i][3] = fmaf(__uint_as_float(v[u][i][1] & 0xffff0000u), wgt, acc[i][3]);
+        }
       }
     }
     const float inv = 1.0f / lsum;
-    CB_GLOBAL uintx4* dst = (CB_GLOBAL uintx4*)((CB_GLOBAL uint16_t*)p.out + gr * D + slice * DPT);
+    CB_GLOBAL uint16_t* orow = gout + grow[rr] * D;
 #pragma unroll
-    for (int i = 0; i < DPT / 8; i++) {
-      uintx4 pk;
-      pk[0] = (uint32_t)f2bf(acc[8 * i + 0] * inv) | ((uint32_t)f2bf(acc[8 * i + 1] * inv) << 16);
-      pk[1] = (uint32_t)f2bf(acc[8 * i + 2] * inv) | ((uint32_t)f2bf(acc[8 * i + 3] * inv) << 16);
-      pk[2] = (uint32_t)f2bf(acc[8 * i + 4] * inv) | ((uint32_t)f2bf(acc[8 * i + 5] * inv) << 16);
-      pk[3] = (uint32_t)f2bf(acc[8 * i + 6] * inv) | ((uint32_t)f2bf(acc[8 * i + 7] * inv) << 16);
-      dst[i] = pk;
+    for (int i = 0; i < NDT; i++) {
+      uintx2 pk;
+      pk[0] = (uint32_t)f2bf(acc[i][0] * inv) | ((uint32_t)f2bf(acc[i][1] * inv) << 16);
+      pk[1] = (uint32_t)f2bf(acc[i][2] * inv) | ((uint32_t)f2bf(acc[i][3] * inv) << 16);
+      *(CB_GLOBAL uintx2*)(orow + 16 * (dt0 + i) + 4 * kg) = pk;
     }
   }
 }
@@ -695,9 +700,14 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 
   if constexpr (kHookEarly) hook->stamp(3);
   // Buffer descriptor over this sequence's partials (byte offsets fit 32 bits, checked by the launcher).
-  const int64_t seq_row0 = (int64_t)off * p.Hq;
   const __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc(
-      reinterpret_cast<char*>(p.partial) + seq_row0 * p.nsplit * kPartialBytes, 0, 0x7fffffff, 0x00020000);
+      reinterpret_cast<char*>(p.partial) + unit_tile0(off, p.Hq, p.Hkv, b) * p.nsplit * kUnitBytes, 0, 0x7fffffff, 0x00020000);
+  uint32_t ubyte[R];  // split 0's unit of each of this wave's row tiles
+#pragma unroll
+  for (int rr = 0; rr < R; rr++) {
+    const int ti = (row0 >> 4) + (SEQ ? w : wi) * R + rr;
+    ubyte[rr] = (uint32_t)(hk * ((M + 15) >> 4) + ti) * (uint32_t)p.nsplit * (uint32_t)kUnitBytes;
+  }
   // finish.  Every lane holds its query's full denominator.
   {
 #pragma unroll
@@ -719,22 +729,22 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
       } else {
         // partial state of this split, written through to memory (agent scope) so that the merging
         // workgroup, possibly on another XCD with its own L2, can read it without cache flushes
-        const uint32_t pbyte = (uint32_t)(((grow[rr] - seq_row0) * p.nsplit + split) * kPartialBytes);
+        const uint32_t pbyte = ubyte[rr] + (uint32_t)split * kUnitBytes;
 #pragma unroll
         for (int i = 0; i < ndt; i++) {
           const floatx4 o = (kTwoGroups && gi == 1) ? st.o[rr][(4 + i) & 7] : st.o[rr][i];
           const int dt = dt0 + i;
           const uintx2 v = {(uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16),
                             (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16)};
-          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, 0);
-          else __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + (16 * dt + 4 * kg) * 2, 0, kAgentCoherent);
+          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + dt * 512 + l * 8, 0, 0);
+          else __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + dt * 512 + l * 8, 0, kAgentCoherent);
         }
         if (kg == 0 && (!kTwoGroups || gi == 0)) {
           // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
           const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
           const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
-          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, 0);
-          else __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + D * 2, 0, kAgentCoherent);
+          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + kUnitMl + c * 8, 0, 0);
+          else __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + kUnitMl + c * 8, 0, kAgentCoherent);
         }
       }
     }
@@ -788,8 +798,8 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   if (!last_flag) return;
   // Same XCD: the write-through stores left the lines in this L2, plain (cached) loads are coherent
   // with them.  Otherwise read past the L2 with agent-coherent loads.
-  if (last_flag == 1) merge_rows<RT, G, 0>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
-  else merge_rows<RT, G, kAgentCoherent>(p, prsrc, seq_row0, row0, M, g, off, hk, nsplit_b, tid);
+  if (last_flag == 1) merge_tile<R, ndt, 0>(prsrc, grow, ubyte, gout, nsplit_b, dt0, l);
+  else merge_tile<R, ndt, kAgentCoherent>(prsrc, grow, ubyte, gout, nsplit_b, dt0, l);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   CB_TS(7);
 #undef CB_TS
@@ -822,34 +832,39 @@ __global__ __launch_bounds__(256 * G) void k_verify_mfma(AttnParams p, SeqMeta m
 }
 
 // Stand-alone merge of the bf16 partials, used when a tile's partials are too many for one
-// workgroup to pull through its compute unit: 16 rows per workgroup, thread -> (row, 8-dim slice).
-__global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMeta meta, int total_rows) {
+// workgroup to pull through its compute unit: one wave per 16-row tile, lane (kg, c) -> row c, dims
+// 16 dt + 4 kg + {0..3} of all 8 dim tiles, as the partials are laid out.
+// grid: x = groups of 4 row tiles, y = kv head, z = sequence; block = 256 threads.
+__global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMeta meta) {
   constexpr int D = 128;
-  const int tid = threadIdx.x;
-  const int64_t gr = (int64_t)blockIdx.x * 16 + (tid >> 4);
-  if (gr >= total_rows) return;
-  const int slice = tid & 15;
-  const int node = (int)(gr / p.Hq);
-  int b = 0;
-  while (b + 1 < p.batch && node >= meta.node_off[b + 1]) b++;
-  const int len = meta.kv_len[b] + (meta.node_off[b + 1] - meta.node_off[b]);
+  const int l = threadIdx.x & 63, c = l & 15, kg = l >> 4;
+  const int b = blockIdx.z, hk = blockIdx.y;
+  const int ti = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int g = p.Hq / p.Hkv;
+  const int off = meta.node_off[b], N = meta.node_off[b + 1] - off;
+  const int M = N * g;
+  const int row = ti * 16 + c;
+  if (row >= M) return;
+  const int len = meta.kv_len[b] + N;
   const int ns = (len + p.chunk - 1) / p.chunk;
   if (ns <= 1) return;  // the attention kernel already wrote the output
-  const char* pr = reinterpret_cast<const char*>(p.partial) + gr * p.nsplit * kPartialBytes;
-  float acc[8];
+  const char* pr = reinterpret_cast<const char*>(p.partial) +
+                   (unit_tile0(off, p.Hq, p.Hkv, b) + (int64_t)hk * ((M + 15) >> 4) + ti) * p.nsplit * kUnitBytes;
+  floatx4 acc[8];
 #pragma unroll
-  for (int i = 0; i < 8; i++) acc[i] = 0.f;
+  for (int i = 0; i < 8; i++) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
   float lsum = 0.f, m_run = -INFINITY;
-  constexpr int BS = 8;
+  constexpr int BS = 4;
   for (int t0 = 0; t0 < ns; t0 += BS) {
-    uint4 v[BS];
+    uint2 v[BS][8];
     float2 ml[BS];
 #pragma unroll
     for (int u = 0; u < BS; u++) {
       const int t = (t0 + u < ns) ? t0 + u : ns - 1;
-      const char* tb = pr + (int64_t)t * kPartialBytes;
-      ml[u] = *reinterpret_cast<const float2*>(tb + D * 2);
-      v[u] = *reinterpret_cast<const uint4*>(tb + slice * 16);
+      const char* tb = pr + (int64_t)t * kUnitBytes;
+      ml[u] = *reinterpret_cast<const float2*>(tb + kUnitMl + c * 8);
+#pragma unroll
+      for (int i = 0; i < 8; i++) v[u][i] = *reinterpret_cast<const uint2*>(tb + i * 512 + l * 8);
     }
     float mb = -INFINITY;
 #pragma unroll
@@ -865,21 +880,31 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
     for (int u = 0; u < BS; u++) {
       const float wgt = (t0 + u < ns && ml[u].x != -INFINITY) ? __expf(ml[u].x - m_new) : 0.f;
       lsum = fmaf(ml[u].y, wgt, lsum);
-      const uint32_t wv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
-      for (int k = 0; k < 4; k++) {
-        acc[2 * k] = fmaf(__uint_as_float(wv[k] << 16), wgt, acc[2 * k]);
-        acc[2 * k + 1] = fmaf(__uint_as_float(wv[k] & 0xffff0000u), wgt, acc[2 * k + 1]);
+      for (int i = 0; i < 8; i++) {
+        acc[i][0] = fmaf(__uint_as_float(v[u][i].x << 16), wgt, acc[i][0]);
+        acc[i][1] = fmaf(__uint_as_float(v[u][i].x & 0xffff0000u), wgt, acc[i][1]);
+        acc[i][2] = fmaf(__uint_as_float(v[u][i].y << 16), wgt, acc[i][2]);
+        acc[i][3] = fmaf(__uint_as_float(v[u][i].y & 0xffff0000u), wgt, acc[i][3]);
       }
     }
   }
   const float inv = 1.0f / lsum;
-  uint4 pk;
-  pk.x = (uint32_t)f2bf(acc[0] * inv) | ((uint32_t)f2bf(acc[1] * inv) << 16);
-  pk.y = (uint32_t)f2bf(acc[2] * inv) | ((uint32_t)f2bf(acc[3] * inv) << 16);
-  pk.z = (uint32_t)f2bf(acc[4] * inv) | ((uint32_t)f2bf(acc[5] * inv) << 16);
-  pk.w = (uint32_t)f2bf(acc[6] * inv) | ((uint32_t)f2bf(acc[7] * inv) << 16);
-  *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(p.out) + gr * D + slice * 8) = pk;
+  const int node = row / g, hg = row - node * g;
+  uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + ((int64_t)(off + node) * p.Hq + hk * g + hg) * D;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    uint2 pk;
+    pk.x = (uint32_t)f2bf(acc[i][0] * inv) | ((uint32_t)f2bf(acc[i][1] * inv) << 16);
+    pk.y = (uint32_t)f2bf(acc[i][2] * inv) | ((uint32_t)f2bf(acc[i][3] * inv) << 16);
+    *reinterpret_cast<uint2*>(orow + 16 * i + 4 * kg) = pk;
+  }
+}
+
+size_t attn_mfma_partial_bytes(size_t max_total_nodes, int Hq, int Hkv, int max_batch, int max_splits) {
+  // the last sequence's units end at or before tile max_total_nodes * Hq / 16 + (Hkv + 1) * max_batch
+  const size_t tiles = max_total_nodes * Hq / 16 + (size_t)(Hkv + 1) * max_batch + 1;
+  return tiles * (size_t)max_splits * kUnitBytes;
 }
 
 bool attn_mfma_supports(const AttnParams& p) {
@@ -890,7 +915,7 @@ bool attn_mfma_supports(const AttnParams& p) {
   }
   if (p.nsplit > 4096) return false;  // the ticket counts arrivals in 16 bits
   // partial offsets inside one sequence are 32-bit byte offsets of a buffer descriptor
-  if ((int64_t)CB_MAX_NODES * p.Hq * p.nsplit * kPartialBytes >= (1ll << 31)) return false;
+  if ((int64_t)p.Hkv * ((CB_MAX_NODES * (p.Hq / p.Hkv) + 15) / 16) * p.nsplit * kUnitBytes >= (1ll << 31)) return false;
   return true;
 }
 
@@ -930,7 +955,7 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   q.grid_z = grid.z;
   // one workgroup can pull about 50 GB/s of partials through its compute unit: beyond a few hundred
   // KiB per tile a separate, fully parallel merge kernel is cheaper than the in-kernel merge
-  q.external_merge = (p.nsplit > 1 && (int64_t)p.nsplit * rt_rows * kPartialBytes > 320 * 1024) ? 1 : 0;
+  q.external_merge = (p.nsplit > 1 && (int64_t)p.nsplit * (rt_rows / 16) * kUnitBytes > 320 * 1024) ? 1 : 0;
   if (p.debug_flags & 256) q.external_merge = 1;  // (timing aid)
   if (logits_work) {
     const LogitsWork& lw = *logits_work;
@@ -944,8 +969,8 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (q.external_merge && !(p.debug_flags & 1)) {
-    const int total_rows = total_nodes * p.Hq;
-    hipLaunchKernelGGL(k_merge_partials_bf16, dim3((total_rows + 15) / 16), dim3(256), 0, st, q, meta, total_rows);
+    const int tiles16 = (M + 15) / 16;
+    hipLaunchKernelGGL(k_merge_partials_bf16, dim3((tiles16 + 3) / 4, p.Hkv, p.batch), dim3(256), 0, st, q, meta);
     e = hipGetLastError();
   }
   return e;

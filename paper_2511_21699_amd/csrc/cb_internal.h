@@ -188,6 +188,8 @@ hipError_t launch_attn_simt(hipStream_t st, const AttnParams& p, const SeqMeta& 
                             int max_nodes_in_call);
 hipError_t launch_merge(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype, int total_nodes);
 int attn_mfma_tile_rows(int mrows);            // rows per workgroup tile chosen for a given g*N
+// bytes the MFMA path's partial states can take (its own layout, padded to 16-row tiles per kv head)
+size_t attn_mfma_partial_bytes(size_t max_total_nodes, int Hq, int Hkv, int max_batch, int max_splits);
 bool attn_mfma_supports(const AttnParams& p);  // shape/geometry the MFMA kernel takes (bf16 is the caller's check)
 bool attn_mfma_can_fuse(const AttnParams& p, int max_nodes_in_call, int64_t logits_items, int logits_dtype);
 // with logits_work != nullptr (only if attn_mfma_can_fuse) the same launch also scans the logits and runs the acceptance
