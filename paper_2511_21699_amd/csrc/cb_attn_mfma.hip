@@ -832,14 +832,15 @@ __global__ __launch_bounds__(256 * G) void k_verify_mfma(AttnParams p, SeqMeta m
 }
 
 // Stand-alone merge of the bf16 partials, used when a tile's partials are too many for one
-// workgroup to pull through its compute unit: one wave per 16-row tile, lane (kg, c) -> row c, dims
-// 16 dt + 4 kg + {0..3} of all 8 dim tiles, as the partials are laid out.
-// grid: x = groups of 4 row tiles, y = kv head, z = sequence; block = 256 threads.
+// workgroup to pull through its compute unit: one workgroup per 16-row tile, its four waves take two
+// dim tiles each; lane (kg, c) -> row c, dims 16 dt + 4 kg + {0..3}, as the partials are laid out.
+// grid: x = 16-row tile, y = kv head, z = sequence; block = 256 threads.
 __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMeta meta) {
   constexpr int D = 128;
+  constexpr int NDT = 2;
   const int l = threadIdx.x & 63, c = l & 15, kg = l >> 4;
-  const int b = blockIdx.z, hk = blockIdx.y;
-  const int ti = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int dt0 = (threadIdx.x >> 6) * NDT;
+  const int b = blockIdx.z, hk = blockIdx.y, ti = blockIdx.x;
   const int g = p.Hq / p.Hkv;
   const int off = meta.node_off[b], N = meta.node_off[b + 1] - off;
   const int M = N * g;
@@ -850,13 +851,13 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
   if (ns <= 1) return;  // the attention kernel already wrote the output
   const char* pr = reinterpret_cast<const char*>(p.partial) +
                    (unit_tile0(off, p.Hq, p.Hkv, b) + (int64_t)hk * ((M + 15) >> 4) + ti) * p.nsplit * kUnitBytes;
-  floatx4 acc[8];
+  floatx4 acc[NDT];
 #pragma unroll
-  for (int i = 0; i < 8; i++) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < NDT; i++) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
   float lsum = 0.f, m_run = -INFINITY;
-  constexpr int BS = 4;
+  constexpr int BS = 8;
   for (int t0 = 0; t0 < ns; t0 += BS) {
-    uint2 v[BS][8];
+    uint2 v[BS][NDT];
     float2 ml[BS];
 #pragma unroll
     for (int u = 0; u < BS; u++) {
@@ -864,7 +865,7 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
       const char* tb = pr + (int64_t)t * kUnitBytes;
       ml[u] = *reinterpret_cast<const float2*>(tb + kUnitMl + c * 8);
 #pragma unroll
-      for (int i = 0; i < 8; i++) v[u][i] = *reinterpret_cast<const uint2*>(tb + i * 512 + l * 8);
+      for (int i = 0; i < NDT; i++) v[u][i] = *reinterpret_cast<const uint2*>(tb + (dt0 + i) * 512 + l * 8);
     }
     float mb = -INFINITY;
 #pragma unroll
@@ -873,7 +874,7 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
     const float m_new = fmaxf(m_run, mb);
     const float resc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
 #pragma unroll
-    for (int i = 0; i < 8; i++) acc[i] *= resc;
+    for (int i = 0; i < NDT; i++) acc[i] *= resc;
     lsum *= resc;
     m_run = m_new;
 #pragma unroll
@@ -881,7 +882,7 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
       const float wgt = (t0 + u < ns && ml[u].x != -INFINITY) ? __expf(ml[u].x - m_new) : 0.f;
       lsum = fmaf(ml[u].y, wgt, lsum);
 #pragma unroll
-      for (int i = 0; i < 8; i++) {
+      for (int i = 0; i < NDT; i++) {
         acc[i][0] = fmaf(__uint_as_float(v[u][i].x << 16), wgt, acc[i][0]);
         acc[i][1] = fmaf(__uint_as_float(v[u][i].x & 0xffff0000u), wgt, acc[i][1]);
         acc[i][2] = fmaf(__uint_as_float(v[u][i].y << 16), wgt, acc[i][2]);
@@ -893,11 +894,11 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
   const int node = row / g, hg = row - node * g;
   uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + ((int64_t)(off + node) * p.Hq + hk * g + hg) * D;
 #pragma unroll
-  for (int i = 0; i < 8; i++) {
+  for (int i = 0; i < NDT; i++) {
     uint2 pk;
     pk.x = (uint32_t)f2bf(acc[i][0] * inv) | ((uint32_t)f2bf(acc[i][1] * inv) << 16);
     pk.y = (uint32_t)f2bf(acc[i][2] * inv) | ((uint32_t)f2bf(acc[i][3] * inv) << 16);
-    *reinterpret_cast<uint2*>(orow + 16 * i + 4 * kg) = pk;
+    *reinterpret_cast<uint2*>(orow + 16 * (dt0 + i) + 4 * kg) = pk;
   }
 }
 
@@ -970,7 +971,7 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   if (e != hipSuccess) return e;
   if (q.external_merge && !(p.debug_flags & 1)) {
     const int tiles16 = (M + 15) / 16;
-    hipLaunchKernelGGL(k_merge_partials_bf16, dim3((tiles16 + 3) / 4, p.Hkv, p.batch), dim3(256), 0, st, q, meta);
+    hipLaunchKernelGGL(k_merge_partials_bf16, dim3(tiles16, p.Hkv, p.batch), dim3(256), 0, st, q, meta);
     e = hipGetLastError();
   }
   return e;
