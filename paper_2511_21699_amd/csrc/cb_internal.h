@@ -150,8 +150,9 @@ struct AttnParams {
   KvAddr kv;
   const uint32_t* anc;  // [sumN][kAncWords] (scalar kernel; the MFMA kernel builds the sets itself)
   const int32_t* parent;  // [sumN] device tree, local parent indices
-  float* partial;       // [sumN*Hq][nsplit][partial_stride(D)]: o[D] (unnormalised), m, l, pad
-  uint32_t* tickets;    // one counter per (sequence, kv head, row tile)
+  float* partial;       // split partials; scalar kernel: [sumN*Hq][nsplit][partial_stride(D)]: o[D] (unnormalised), m, l, pad;
+                        // the MFMA kernel has its own bf16 layout (cb_attn_mfma.hip)
+  uint32_t* tickets;    // one 64-bit ticket word per (sequence, kv head, row tile)
   int32_t Hq, Hkv, D;
   int32_t chunk;        // keys per split
   int32_t nsplit;       // partial slots per row (>= splits any sequence uses)
