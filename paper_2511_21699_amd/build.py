@@ -14,6 +14,9 @@ LIB = os.path.join(HERE, "libcacheback_verify.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # every atomic here is issued by one thread; the wave-aggregation pass would only add a
+         # wait for the result right behind the atomic, where the kernels want it in flight
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

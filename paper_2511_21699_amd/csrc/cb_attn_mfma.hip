@@ -33,6 +33,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned uintx4;
 typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned uintx2;
 #define CB_GLOBAL __attribute__((address_space(1)))
+#define CB_LDS __attribute__((address_space(3)))
 constexpr int kAgentCoherent = 16;  // buffer cache policy: sc1 = coherent at agent (device) scope
 
 constexpr int kStageKeys = 32;                 // keys per LDS stage and wave group
@@ -60,6 +61,17 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   // s_waitcnt simm16 on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// A 16-byte global load that the compiler does not know to be one.  It orders every load it tracks
+// against the LDS-DMA requests of the ring as if the two kinds could overtake each other: the first
+// use of a tracked load's result while ring requests are in flight costs a wait for all of them.
+// Loads return in the order they were issued, so the ring's own counted waits cover these; the
+// caller pins the result (asm "+v") behind such a wait before it touches it.
+__device__ __forceinline__ uintx4 load_b128_untracked(const CB_GLOBAL void* p) {
+  uintx4 r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  return r;
 }
 
 __device__ __forceinline__ uint16_t f2bf(float x) {
@@ -98,6 +110,18 @@ __device__ __forceinline__ void ring_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// One LDS-DMA request: every lane's 16 bytes at `src` go to LDS at dst + lane * 16 (dst is the same
+// in all lanes of the wave).  Written as an instruction the compiler does not interpret: for the
+// builtin it keeps its own account of which request has landed, cannot relate the ring's counted
+// waits to the conditional refills, and puts a wait for everything in flight in front of the
+// stages' LDS reads (and in front of the loop, for the query registers).  Here every wait is the
+// ring's own: a stage's wait and barrier come before any read of its slot, and each of these
+// statements is a compiler barrier for memory accesses.
+__device__ __forceinline__ void lds_dma_b128(const CB_GLOBAL char* src, CB_LDS uint4* dst) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory");
+}
+
 // Wave `w` brings rows 8w..8w+7 of stage `s` (keys key0..key0+31) into the ring slot: two 1 KiB
 // loads for K and two for V.  LDS position of a 16-byte piece is fixed by the lane (row*16 + c);
 // which piece of the row lands there is chosen by the XOR swizzle so that the MFMA operand reads
@@ -114,10 +138,8 @@ __device__ __forceinline__ void issue_stage(uint4* kdst, uint4* vdst, const KeyA
     const int64_t off = ka.byte_off(key);
     const int pk = c ^ (r & 15);
     const int pv = c ^ ((r & 7) << 1);
-    __builtin_amdgcn_global_load_lds((const CB_GLOBAL uint32_t*)(kbase + off + pk * 16),
-                                     (__attribute__((address_space(3))) void*)(kdst + (8 * w + 4 * i) * 16), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const CB_GLOBAL uint32_t*)(vbase + off + pv * 16),
-                                     (__attribute__((address_space(3))) void*)(vdst + (8 * w + 4 * i) * 16), 16, 0, 0);
+    lds_dma_b128(kbase + off + pk * 16, (CB_LDS uint4*)kdst + (8 * w + 4 * i) * 16);
+    lds_dma_b128(vbase + off + pv * 16, (CB_LDS uint4*)vdst + (8 * w + 4 * i) * 16);
   }
 }
 
@@ -472,7 +494,7 @@ __device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const i
 // are registers to spare and its first item is woven into the tail of the attention (see LogitsHook).
 template <int R, int G, bool SEQ, bool FUSE>
 __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMetaLanes& ml, unsigned long long ts0,
-                                          LogitsHook<256 * G>* hook) {
+                                          LogitsHook<256 * G>* hook, unsigned long long* ts_sh) {
   constexpr bool kHookEarly = FUSE && R == 1;
   static_assert(G == 1 || (G == 2 && R <= 2), "two wave groups are built for one or two row tiles per wave");
   constexpr int RT = 64 * R * (SEQ ? G : 1);  // rows of the workgroup's tile
@@ -518,10 +540,17 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   const int g = p.Hq / p.Hkv;
   const SeqShape shp = seq_shape(ml, b);
   const int wg_linear = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
-  CB_GLOBAL unsigned long long* ts = (CB_GLOBAL unsigned long long*)p.dbg_ts + (int64_t)wg_linear * 8;
+  // (timing aid: the stamps go to LDS and are copied out when the kernel ends -- a store to memory
+  // here, even one that never executes, makes the compiler treat the loads in flight as unordered
+  // and wait for all of them wherever it needs one)
+  CB_LDS unsigned long long* ts = (CB_LDS unsigned long long*)ts_sh;
   const bool do_ts = (p.debug_flags & 32) && threadIdx.x == 0 && wg_linear < 1024;
 #define CB_TS(i) do { if (do_ts) ts[i] = wall_clock64(); } while (0)
-  if (do_ts) ts[0] = ts0;
+  if (do_ts) {
+#pragma unroll
+    for (int i = 1; i < 16; i++) ts[i] = 0;
+    ts[0] = ts0;
+  }
   CB_TS(1);
   const int off = shp.off, N = shp.N, S = shp.S;
   const int M = N * g;
@@ -549,6 +578,11 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     ka.bt_first = first;
     __syncthreads();  // the K/V addresses below depend on it
   }
+  // The workgroup's logits item is requested first of all, into registers.  Loads return in the
+  // order of their requests, so wherever these sit they hold up what was requested behind them for
+  // as long as they take (cold pages of another buffer); in front of the K/V prologue that time
+  // overlaps with the prologue's own first-data latency, and the first stage's wait covers them.
+  if constexpr (kHookEarly) hook->prefetch_first();
   // Everything this workgroup needs from memory is requested up front, oldest first: the query rows
   // and ancestor words (to registers), then NS-1 stages of K/V (to LDS).
   WaveState<R> st;
@@ -568,7 +602,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     grow[rr] = valid ? gr : -1;
     const CB_GLOBAL uintx4* qp = (const CB_GLOBAL uintx4*)(gq + gr * D);
 #pragma unroll
-    for (int ds = 0; ds < 4; ds++) st.q[rr][ds] = __builtin_bit_cast(bf16x8, qp[kg + 4 * ds]);
+    for (int ds = 0; ds < 4; ds++) st.q[rr][ds] = __builtin_bit_cast(bf16x8, load_b128_untracked(qp + kg + 4 * ds));
 #pragma unroll
     for (int dt = 0; dt < 8; dt++) st.o[rr][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
     st.lacc[rr] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -590,19 +624,32 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 #define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * SK, last_key, w, l)
   const bool fine_ts = (p.debug_flags & 1024) != 0;  // (timing aid: slots 5-7 stamp the issue phase instead)
   if (fine_ts) CB_TS(5);
-  if (!(p.debug_flags & 4)) {  // (timing aid: bit 2 leaves the loads out, bit 1 the arithmetic)
-    if (0 < nst) CB_ISSUE(0, 0);
-    if (fine_ts) CB_TS(6);
-    if (1 < nst) CB_ISSUE(1, 1);
-    if (fine_ts) CB_TS(7);
-    if (2 < nst) CB_ISSUE(2, 2);
-  }
+  // The prologue always requests NS-1 stages (keys past the split are clamped to valid ones and
+  // never used), unconditionally: the compiler then knows that the query loads above have at least
+  // that many requests behind them, and that the first stage's wait below covers them.  With a
+  // conditional prologue it waits for everything in flight before the first MFMA.
+  CB_ISSUE(0, 0);
+  if (fine_ts) CB_TS(6);
+  CB_ISSUE(1, 1);
+  if (fine_ts) CB_TS(7);
+  CB_ISSUE(2, 2);
+  const int nst_w = nst < NS - 1 ? NS - 1 : nst;  // stages requested
   CB_TS(2);
-  // The workgroup's logits item is requested behind the K/V prologue, into registers, and used after
-  // the sweep.  The ring's waits count the newest requests a wave may leave in flight (vmcnt <= 8,
-  // 4, 0); these extra loads only make such a wait cover more than it needs to, never less.
-  if constexpr (kHookEarly) hook->prefetch_first();
   if (tree_split) build_ancestor_sets(anc_sh, N, my_parent, jump_rounds(p.max_depth));  // uniform in the workgroup; hidden behind the first K/V wait
+  // The first stage's wait, outside the ring loop: it also covers the query loads (older than the
+  // whole prologue), whose registers are pinned here.
+  wait_vmcnt<8>();
+  ring_barrier();
+#pragma unroll
+  for (int rr = 0; rr < R; rr++)
+#pragma unroll
+    for (int ds = 0; ds < 4; ds++) asm volatile("" : "+v"(st.q[rr][ds]));
+  CB_TS(3);
+  // The logits item rides on the sweep's waits and barriers: its reduction here (its loads are
+  // older still than the query's), the combination of the waves' candidates and the partial's
+  // store behind the first stage's barrier, the scan ticket at the last stage, whose vmcnt(0)
+  // covers that store.
+  if constexpr (kHookEarly) hook->mid_consume();
 
 // the row tiles of a wave that lie past the sequence's rows are left out (R = 2: all, one or none)
 #define CB_COMPUTE(kp, vp, key0, need_mask)                                                                    \
@@ -613,21 +660,29 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     if (nvt == R) compute_stage<R, R>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);  \
     else if (R > 1) compute_stage<R, 1>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);\
   } while (0)
+#define CB_STAGE_COMPUTE(J, s)                                                                     \
+  _Pragma("unroll") for (int h = SEQ ? 0 : gi; h < (SEQ ? G : gi + 1); h++) {                      \
+    const int key0 = k0 + (s) * SK + h * kStageKeys;                                               \
+    const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                        \
+    if (key0 < k1 && nvt > 0)                                                                      \
+      CB_COMPUTE(K##J + h * kStageVecs, V##J + h * kStageVecs, key0, need_mask);                   \
+  }
 #define CB_STAGE(J, JPREV)                                                                         \
   {                                                                                                \
     const int s = s0 + J;                                                                          \
     if (s < nst) {                                                                                 \
-      const int after = nst - 1 - s; /* stages issued after this one, at most NS-2 */             \
-      if (after >= 2) wait_vmcnt<8>(); else if (after == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); \
-      ring_barrier();                                                                              \
-      if (s == 0) CB_TS(3);                                                                        \
-      if (s + NS - 1 < nst && !(p.debug_flags & 4)) CB_ISSUE(JPREV, s + NS - 1);                   \
-      _Pragma("unroll") for (int h = SEQ ? 0 : gi; h < (SEQ ? G : gi + 1); h++) {                  \
-        const int key0 = k0 + s * SK + h * kStageKeys;                                             \
-        const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                    \
-        if (key0 < k1 && nvt > 0 && !(p.debug_flags & 2))                                          \
-          CB_COMPUTE(K##J + h * kStageVecs, V##J + h * kStageVecs, key0, need_mask);               \
+      { /* (stage 0 was waited for above: the compiler is to see the same wait in front of every */ \
+        /* stage's LDS reads, or it adds one of its own for everything in flight)               */ \
+        const int after = nst_w - 1 - s; /* stages requested after this one, at most NS-2 */      \
+        if (after >= 2) wait_vmcnt<8>(); else if (after == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); \
+        ring_barrier();                                                                            \
       }                                                                                            \
+      if (s + NS - 1 < nst) CB_ISSUE(JPREV, s + NS - 1);                                           \
+      if constexpr (kHookEarly) {                                                                  \
+        if (J == 0 && s0 == 0) hook->mid_combine();                                                \
+        if (s == nst - 1 && nst >= NS - 1) hook->early_ticket(); /* behind this stage's vmcnt(0) */ \
+      }                                                                                            \
+      CB_STAGE_COMPUTE(J, s)                                                                       \
     }                                                                                              \
   }
   for (int s0 = 0; s0 < nst; s0 += NS) {
@@ -636,10 +691,12 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     CB_STAGE(2, 1)
     CB_STAGE(3, 2)
   }
+#undef CB_STAGE_COMPUTE
 #undef CB_STAGE
 #undef CB_COMPUTE
 #undef CB_ISSUE
 
+  if (nst < NS - 1) wait_vmcnt<0>();  // (a short split: the unused rest of the prologue must land before the ring is reused)
   CB_TS(4);
   if (p.debug_flags & 8) return;  // (timing aid: stop after the key sweep)
   if constexpr (kHookEarly) {
@@ -805,11 +862,25 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 #undef CB_TS
 }
 
+// Timing aid (debug bit 5): thread 0 copies the workgroup's stamps from LDS to the table, the
+// attention's eight to row wg, the logits hook's eight to row wg + 512.
+__device__ __forceinline__ void flush_timestamps(const AttnParams& p, const unsigned long long* ts_sh, bool hook_rows) {
+  const int wg = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
+  if (!(p.debug_flags & 32) || threadIdx.x != 0 || wg >= 1024) return;
+  const CB_LDS unsigned long long* ts = (const CB_LDS unsigned long long*)ts_sh;
+  CB_GLOBAL unsigned long long* out = (CB_GLOBAL unsigned long long*)p.dbg_ts;
+  for (int i = 0; i < 8; i++) out[(int64_t)wg * 8 + i] = ts[i];
+  if (hook_rows && wg < 512)
+    for (int i = 0; i < 8; i++) out[(int64_t)(wg + 512) * 8 + i] = ts[8 + i];
+}
+
 template <int R, int G, bool SEQ>
 __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p, SeqMeta meta) {
   const unsigned long long ts0 = wall_clock64();
   const SeqMetaLanes ml = seq_meta_prefetch(meta);
-  attn_tile<R, G, SEQ, false>(p, ml, ts0, nullptr);
+  __shared__ unsigned long long ts_sh[16];
+  attn_tile<R, G, SEQ, false>(p, ml, ts0, nullptr, ts_sh);
+  flush_timestamps(p, ts_sh, false);
 }
 
 // The whole verification in one launch: every workgroup does its attention duty (a tile's split,
@@ -826,9 +897,11 @@ __global__ __launch_bounds__(256 * G) void k_verify_mfma(AttnParams p, SeqMeta m
   __shared__ TailLds tail;
   const int wg = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
   LogitsHook<256 * G> hook(lw, ml, tail, wg);
-  if ((p.debug_flags & 32) && wg < 512) hook.dbg = p.dbg_ts + (int64_t)(wg + 512) * 8;  // (timing aid: second half of the table)
-  attn_tile<R, G, SEQ, true>(p, ml, ts0, &hook);
+  __shared__ unsigned long long ts_sh[16];
+  if (p.debug_flags & 32) hook.dbg = (CB_LDS unsigned long long*)ts_sh + 8;  // (timing aid)
+  attn_tile<R, G, SEQ, true>(p, ml, ts0, &hook, ts_sh);
   hook.finish();
+  flush_timestamps(p, ts_sh, true);
 }
 
 // Stand-alone merge of the bf16 partials, used when a tile's partials are too many for one

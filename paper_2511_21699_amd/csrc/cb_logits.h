@@ -7,6 +7,17 @@
 
 namespace cb {
 
+// Every pointer these functions are handed is device (global) memory, but it reaches them as a
+// generic pointer inside an argument struct.  Accesses through a generic pointer are flat
+// instructions, which the compiler orders behind every outstanding LDS-DMA load (they might touch
+// LDS) -- a vmcnt(0) wait in the middle of the attention kernel's ring.  So each access site casts
+// to the global address space.
+#define CBL_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ CBL_GLOBAL T* as_global(T* p) {
+  return (CBL_GLOBAL T*)p;
+}
+
 __device__ __forceinline__ float elem_to_float(float x) { return x; }
 __device__ __forceinline__ float elem_to_float(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
 
@@ -67,13 +78,13 @@ __device__ __forceinline__ unsigned long long amax_pack(float v, int i) {
 }
 template <bool COHERENT>
 __device__ __forceinline__ void amax_store(ArgmaxPartial* dst, float v, int i) {
-  unsigned long long* p = reinterpret_cast<unsigned long long*>(dst);
+  CBL_GLOBAL unsigned long long* p = (CBL_GLOBAL unsigned long long*)dst;
   if (COHERENT) __hip_atomic_store(p, amax_pack(v, i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   else *p = amax_pack(v, i);
 }
 template <bool COHERENT>
 __device__ __forceinline__ void amax_load(const ArgmaxPartial* src, float& v, int& i) {
-  const unsigned long long* p = reinterpret_cast<const unsigned long long*>(src);
+  const CBL_GLOBAL unsigned long long* p = (const CBL_GLOBAL unsigned long long*)src;
   const unsigned long long x = COHERENT ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
   v = __uint_as_float((uint32_t)x);
   i = (int)(uint32_t)(x >> 32);
@@ -94,26 +105,44 @@ struct ChunkScan {
   static constexpr int VEC = 16 / sizeof(T);
   static constexpr int kVecPerThread = kArgmaxChunk / VEC / NT;
   static_assert(kVecPerThread >= 1, "chunk smaller than one load per thread");
-  uint4 u[kVecPerThread];
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 u[kVecPerThread];
   int64_t start, end, vec_end, nvec;
 
   // (no __restrict__ on the row: the loads must stay where they are written, in front of the
   // caller's later waits, and not drift down to their first use)
+  // UNTRACKED: the loads are issued as instructions the compiler does not know to be loads (it
+  // would wait for every LDS-DMA request in flight at their first use); the caller must have
+  // waited for them (vmcnt) before pin_here() and consume().
+  template <bool UNTRACKED = false>
   __device__ __forceinline__ void issue(const T* base, int64_t V, int c, int tid) {
     start = (int64_t)c * kArgmaxChunk;
     end = (start + kArgmaxChunk < V) ? start + kArgmaxChunk : V;
     const bool aligned = ((reinterpret_cast<uintptr_t>(base + start)) & 15) == 0;
     nvec = aligned ? (end - start) / VEC : 0;
     vec_end = start + nvec * VEC;
-    const uint4* vp = reinterpret_cast<const uint4*>(base + start);
+    const CBL_GLOBAL u32x4* vp = (const CBL_GLOBAL u32x4*)(base + start);
     if (nvec > 0) {  // (uniform; lanes past the end re-read the last vector and ignore it later, so
                      //  the loads are unconditional and nothing has to wait for them here)
 #pragma unroll
       for (int k = 0; k < kVecPerThread; k++) {
         const int64_t i = tid + k * NT;
-        u[k] = vp[i < nvec ? i : nvec - 1];
+        if constexpr (UNTRACKED) {
+          asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(u[k]) : "v"(vp + (i < nvec ? i : nvec - 1)) : "memory");
+        } else {
+          u[k] = vp[i < nvec ? i : nvec - 1];
+        }
       }
     }
+  }
+
+  // Keeps the reduction of the loaded vectors at (or behind) this point of the program: without it
+  // the compiler moves that loop-invariant arithmetic, and the wait for the loads with it, to the
+  // front of the caller's loop.
+  __device__ __forceinline__ void pin_here() {
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; k++)
+      asm volatile("" : "+v"(u[k]));
   }
 
   __device__ __forceinline__ void consume(const T* base, int tid, ScanLds& sh) {
@@ -138,7 +167,7 @@ struct ChunkScan {
         amax_take_later(bv, bi, __uint_as_float(u[k].w), e0 + 3);
       }
     }
-    for (int64_t i = vec_end + tid; i < end; i += NT) amax_take_later(bv, bi, elem_to_float(base[i]), (int)i);
+    for (int64_t i = vec_end + tid; i < end; i += NT) amax_take_later(bv, bi, elem_to_float(as_global(base)[i]), (int)i);
     wave_first_max(bv, bi);
     if ((tid & 63) == 0) { sh.v[tid >> 6] = bv; sh.i[tid >> 6] = bi; }
   }
@@ -202,8 +231,8 @@ __device__ __forceinline__ void accept_sequence(AcceptLds& sh, const AcceptArgs&
   // entries, then its row's partial maxima, four at a time
   int par_raw = -1, tok = 0;
   if (t < N) {
-    par_raw = g.parent[off + t];
-    tok = g.tokens[off + t];
+    par_raw = as_global(g.parent)[off + t];
+    tok = as_global(g.tokens)[off + t];
   }
   int a = -1;
   if (t < N) {
@@ -220,7 +249,7 @@ __device__ __forceinline__ void accept_sequence(AcceptLds& sh, const AcceptArgs&
       for (int u = 0; u < 4; u++) amax_take(bv, bi, v[u], i[u]);
     }
     a = bi;
-    g.argmax_out[off + t] = a;
+    as_global(g.argmax_out)[off + t] = a;
   }
   if (t < CB_MAX_NODES) sh.a[t] = a;
   __syncthreads();
@@ -229,11 +258,11 @@ __device__ __forceinline__ void accept_sequence(AcceptLds& sh, const AcceptArgs&
   if (t < N) {
     // (the same repair as sanitized_parent(): entries outside [0, t) become "child of the root")
     if (t == 0) {
-      if (par_raw != -1) atomicOr(g.status, 1);
+      if (par_raw != -1) __hip_atomic_fetch_or(as_global(g.status), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else {
       par = par_raw;
       if (par < 0 || par >= t) {
-        atomicOr(g.status, 1);
+        __hip_atomic_fetch_or(as_global(g.status), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         par = 0;
       }
     }
@@ -257,7 +286,7 @@ __device__ __forceinline__ void accept_sequence(AcceptLds& sh, const AcceptArgs&
   }
   if (depth > g.max_depth || unresolved >= 0) {  // (an unresolved node is deeper than the rounds reach, hence too deep)
     acc = false;
-    if (t < N) atomicOr(g.status, 2);
+    if (t < N) __hip_atomic_fetch_or(as_global(g.status), 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   uint32_t key = acc ? ((uint32_t)(depth + 1) << 16) | (uint32_t)(0xffff - t) : 0u;
   key = wave_max_u32(key);
@@ -274,16 +303,16 @@ __device__ __forceinline__ void accept_sequence(AcceptLds& sh, const AcceptArgs&
   __syncthreads();
   const int stride = g.max_depth + 1;
   if (t < N && ((sh.best[t >> 5] >> (t & 31)) & 1u)) {
-    g.path[b * stride + depth] = t;
-    g.tok_user[b * stride + depth] = a;
+    as_global(g.path)[b * stride + depth] = t;
+    as_global(g.tok_user)[b * stride + depth] = a;
   }
   if (t > L && t < stride) {
-    g.path[b * stride + t] = -1;
-    g.tok_user[b * stride + t] = -1;
+    as_global(g.path)[b * stride + t] = -1;
+    as_global(g.tok_user)[b * stride + t] = -1;
   }
   if (t == 0) {
-    g.len_ctx[b] = L;
-    g.len_user[b] = L;
+    as_global(g.len_ctx)[b] = L;
+    as_global(g.len_user)[b] = L;
   }
   __syncthreads();
 }
@@ -302,8 +331,8 @@ __device__ __forceinline__ void accept_wave(const AcceptArgs& g, int b, int off,
   const bool live = t < N;
   int par_raw = -1, tok = 0;
   if (live) {
-    par_raw = g.parent[off + t];
-    tok = g.tokens[off + t];
+    par_raw = as_global(g.parent)[off + t];
+    tok = as_global(g.tokens)[off + t];
   }
   int a = -1;
   if (live) {
@@ -320,16 +349,16 @@ __device__ __forceinline__ void accept_wave(const AcceptArgs& g, int b, int off,
       for (int u = 0; u < 4; u++) amax_take(bv, bi, v[u], i[u]);
     }
     a = bi;
-    g.argmax_out[off + t] = a;
+    as_global(g.argmax_out)[off + t] = a;
   }
   int par = -1;
   if (live) {
     if (t == 0) {
-      if (par_raw != -1) atomicOr(g.status, 1);
+      if (par_raw != -1) __hip_atomic_fetch_or(as_global(g.status), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else {
       par = par_raw;
       if (par < 0 || par >= t) {
-        atomicOr(g.status, 1);
+        __hip_atomic_fetch_or(as_global(g.status), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         par = 0;
       }
     }
@@ -353,7 +382,7 @@ __device__ __forceinline__ void accept_wave(const AcceptArgs& g, int b, int off,
   bool acc = live && (mine & ~matched) == 0ull;
   if (live && (depth > g.max_depth || j >= 0)) {
     acc = false;
-    atomicOr(g.status, 2);
+    __hip_atomic_fetch_or(as_global(g.status), 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   uint32_t key = acc ? ((uint32_t)(depth + 1) << 16) | (uint32_t)(0xffff - t) : 0u;
   key = wave_max_u32(key);
@@ -362,18 +391,18 @@ __device__ __forceinline__ void accept_wave(const AcceptArgs& g, int b, int off,
   const unsigned long long on_path = shfl_u64(mine, best);
   const int stride = g.max_depth + 1;
   if (live && ((on_path >> t) & 1ull)) {
-    g.path[b * stride + depth] = t;
-    g.tok_user[b * stride + depth] = a;
+    as_global(g.path)[b * stride + depth] = t;
+    as_global(g.tok_user)[b * stride + depth] = a;
   }
   for (int d = t; d < stride; d += 64) {
     if (d > L) {
-      g.path[b * stride + d] = -1;
-      g.tok_user[b * stride + d] = -1;
+      as_global(g.path)[b * stride + d] = -1;
+      as_global(g.tok_user)[b * stride + d] = -1;
     }
   }
   if (t == 0) {
-    g.len_ctx[b] = L;
-    g.len_user[b] = L;
+    as_global(g.len_ctx)[b] = L;
+    as_global(g.len_user)[b] = L;
   }
 }
 
@@ -412,10 +441,12 @@ struct LogitsHook {
   TailLds& sh;
   int wg;
   int state;  // 0 untouched, 1 partial stored but not counted, 2 no item, 3 counted, 4 loads in flight,
-              // 6 counted and, where it fell to this workgroup, accepted
+              // 5 the waves' candidates are in LDS (not yet combined), 6 counted and, where it fell to
+              // this workgroup, accepted, 7 partial stored and its ticket already drawn (early_old)
+  uint32_t early_old = 0;  // thread 0: what the early ticket returned
   int b0;     // the item's sequence
   ChunkScan<uint16_t, NT> pre;
-  unsigned long long* dbg = nullptr;  // timing aid: 8 timestamps of finish() (thread 0), or null
+  __attribute__((address_space(3))) unsigned long long* dbg = nullptr;  // timing aid: 8 timestamps (thread 0) in LDS, or null
 
   __device__ __forceinline__ LogitsHook(const LogitsWork& lw_, const SeqMetaLanes& ml_, TailLds& sh_, int wg_)
       : lw(lw_), ml(ml_), sh(sh_), wg(wg_), state(0), b0(0) {}
@@ -427,6 +458,8 @@ struct LogitsHook {
     if (dbg != nullptr && threadIdx.x == 0) dbg[i] = wall_clock64();
   }
 
+  // after prefetch_first(): whether every thread has ChunkScan::kVecPerThread loads in flight
+  __device__ __forceinline__ bool loads_in_flight() const { return state == 4 && pre.nvec > 0; }
   __device__ __forceinline__ void prefetch_first() {
     if (state != 0) return;
     const int nchunks = lw.accept.nchunks;
@@ -437,14 +470,23 @@ struct LogitsHook {
     const int row = wg / nchunks;
     // sequence of the row: the number of sequences that end at or before it
     b0 = __popcll(__ballot((int)(threadIdx.x & 63) < lw.batch - 1 && ml.o1 <= row));
-    pre.issue(row_base(), lw.V, wg - row * nchunks, threadIdx.x);
+    pre.template issue<true>(row_base(), lw.V, wg - row * nchunks, threadIdx.x);
     state = 4;
   }
-  __device__ __forceinline__ void scan_first() {
-    prefetch_first();
-    if (state != 4) return;
+  // The scan in pieces, for a caller that has barriers of its own to offer (all threads call each):
+  // mid_consume() once the prefetched loads have landed (a vmcnt wait of the caller's that covers
+  // them: the compiler does not track them) -- only if the item has no ragged rest,
+  // whose loads would have to be waited for on the spot --, a workgroup barrier, mid_combine(), and,
+  // once a vmcnt(0) wait of the first wave has followed, early_ticket().  Whatever has not happened
+  // by then, scan_first() and the ticket calls below catch up on.
+  __device__ __forceinline__ void mid_consume() {
+    if (state != 4 || pre.vec_end != pre.end) return;
+    pre.pin_here();
     pre.consume(row_base(), threadIdx.x, sh.scan);
-    __syncthreads();  // the waves' candidates are in LDS
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the candidate is in LDS before the caller's barrier
+    state = 5;
+  }
+  __device__ __forceinline__ void combine_and_store() {
     if (threadIdx.x == 0) {
       float bv;
       int bi;
@@ -453,22 +495,44 @@ struct LogitsHook {
     }
     state = 1;
   }
+  __device__ __forceinline__ void mid_combine() {
+    if (state == 5) combine_and_store();
+  }
+  __device__ __forceinline__ void early_ticket() {
+    if (state != 1) return;
+    if (threadIdx.x == 0)
+      early_old = __hip_atomic_fetch_add(as_global(lw.tickets) + b0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    state = 7;
+  }
+  __device__ __forceinline__ void scan_first() {
+    prefetch_first();
+    if (state == 4) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the item's loads (not tracked by the compiler)
+      pre.pin_here();
+      pre.consume(row_base(), threadIdx.x, sh.scan);
+      state = 5;
+    }
+    if (state != 5) return;
+    __syncthreads();  // the waves' candidates are in LDS
+    combine_and_store();
+  }
   // One thread only -- the one that stored the partial -- after a vmcnt(0) wait that followed
   // scan_first() and before a workgroup barrier.  In two halves so that the caller can put an atomic
   // of its own between them and have both in flight together.
   __device__ __forceinline__ uint32_t ticket_first_issue() const {
-    return state == 1 ? __hip_atomic_fetch_add(lw.tickets + b0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+    if (state == 7) return early_old;
+    return state == 1 ? __hip_atomic_fetch_add(as_global(lw.tickets) + b0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
   }
   __device__ __forceinline__ void ticket_first_resolve(uint32_t old) {
-    if (state != 1) return;
+    if (state != 1 && state != 7) return;
     const uint32_t expect = (uint32_t)node_count(b0) * (uint32_t)lw.accept.nchunks;
     const bool last = old + 1u == expect;
-    if (last) __hip_atomic_store(lw.tickets + b0, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+    if (last) __hip_atomic_store(as_global(lw.tickets) + b0, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
     sh.flag0 = last ? 1 : 0;
   }
   // all threads, after the barrier that followed the ticket
   __device__ __forceinline__ void first_counted() {
-    if (state == 1) state = 3;
+    if (state == 1 || state == 7) state = 3;
   }
   // all threads, after first_counted(): the acceptance, if this workgroup's ticket completed the
   // sequence -- by the first wave alone, the other waves go on at once
@@ -482,7 +546,7 @@ struct LogitsHook {
     const bool stamp = dbg != nullptr && threadIdx.x == 0;
     if (stamp) dbg[0] = wall_clock64();
     scan_first();
-    if (state == 1) {
+    if (state == 1 || state == 7) {
       if (threadIdx.x == 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         ticket_first_resolve(ticket_first_issue());
