@@ -491,7 +491,8 @@ __device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const i
 // has 64*R*G rows -- and walks through all G key halves of a stage itself, so K/V is read from HBM
 // once for a tile of up to 256 rows.
 // `hook` (FUSE only) is the workgroup's share of the logits work; with one row tile per wave there
-// are registers to spare and its first item is woven into the tail of the attention (see LogitsHook).
+// are registers to spare and its item is woven into the attention's own waits and barriers (see
+// LogitsHook).
 template <int R, int G, bool SEQ, bool FUSE>
 __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMetaLanes& ml, unsigned long long ts0,
                                           LogitsHook<256 * G>* hook, unsigned long long* ts_sh) {
@@ -887,7 +888,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p, SeqMeta met
 // perhaps the tile's merge) and takes its share of the logits scan; the workgroup that completes a
 // sequence's scan runs the sequence's acceptance (LogitsHook of cb_logits.h).  The scan does not
 // depend on the attention, so it needs no ordering against it, and its memory round trips ride on
-// those the split merge needs anyway.
+// those the attention needs anyway.
 template <int R, int G, bool SEQ>
 __global__ __launch_bounds__(256 * G) void k_verify_mfma(AttnParams p, SeqMeta meta, LogitsWork lw_arg) {
   const unsigned long long ts0 = wall_clock64();

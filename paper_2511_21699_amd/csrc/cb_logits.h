@@ -425,15 +425,17 @@ struct TailLds {
   int flag0;
 };
 
-// A workgroup's item in steps that the attention code calls where they cost least: the loads behind
-// the first K/V requests (prefetch_first), the scan after the key sweep and its store together with
-// the attention partials' stores (scan_first; one wait covers both), its ticket beside the attention
-// ticket.  The ticket counts the finished items of the item's sequence; the workgroup whose ticket
-// completes the count (every partial is then in memory: each workgroup waited for its own
-// agent-scope store first) has its first wave run the acceptance for that sequence (accept_first).
-// Nobody waits for anybody, so the order in which workgroups run is irrelevant.  finish() does
-// whatever has not been done by then (a workgroup may leave the attention early).  Every method
-// except the ticket halves must be called by all NT threads.
+// A workgroup's item in steps that the attention code calls where they cost least: the loads in
+// front of its first K/V requests (prefetch_first), the reduction once they have landed
+// (mid_consume), the combination of the waves' candidates and the partial's store behind the next
+// barrier (mid_combine), the ticket once a full wait has covered that store (early_ticket); what has
+// not happened by the end of the key sweep is caught up on there (scan_first and the ticket halves,
+// beside the attention's own stores and ticket).  The ticket counts the finished items of the
+// item's sequence; the workgroup whose ticket completes the count (every partial is then in memory:
+// each workgroup waited for its own agent-scope store first) has its first wave run the acceptance
+// for that sequence (accept_first).  Nobody waits for anybody, so the order in which workgroups run
+// is irrelevant.  finish() does whatever has not been done by then (a workgroup may leave the
+// attention early).  Every method except the ticket halves must be called by all NT threads.
 template <int NT>
 struct LogitsHook {
   const LogitsWork& lw;
