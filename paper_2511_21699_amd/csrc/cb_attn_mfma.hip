@@ -401,18 +401,10 @@ __device__ __forceinline__ void pin_args(AttnParams& p) {
   CB_PIN(p.status); CB_PIN(p.dbg_ts);
 }
 __device__ __forceinline__ void pin_logits_args(LogitsWork& w) {
+  // (what the item's scan needs; the acceptance's own arguments are fetched by the one workgroup
+  // that runs it, when it does)
   CB_PIN(w.logits); CB_PIN(w.V); CB_PIN(w.rows); CB_PIN(w.batch); CB_PIN(w.partial_out);
-  CB_PIN(w.tickets); CB_PIN(w.accept.parent); CB_PIN(w.accept.tokens); CB_PIN(w.accept.status);
-  CB_PIN(w.accept.partial); CB_PIN(w.accept.slot_stride); CB_PIN(w.accept.nchunks); CB_PIN(w.accept.max_depth);
-  CB_PIN(w.accept.argmax_out); CB_PIN(w.accept.path); CB_PIN(w.accept.len_ctx); CB_PIN(w.accept.len_user);
-  CB_PIN(w.accept.tok_user);
-  // (the pinned pointers have lost their address space: say again that they are global memory)
-#define CB_REGLOBAL(x) x = (decltype(x))(CB_GLOBAL void*)(x)
-  CB_REGLOBAL(w.logits); CB_REGLOBAL(w.partial_out); CB_REGLOBAL(w.tickets); CB_REGLOBAL(w.accept.parent);
-  CB_REGLOBAL(w.accept.tokens); CB_REGLOBAL(w.accept.status); CB_REGLOBAL(w.accept.partial);
-  CB_REGLOBAL(w.accept.argmax_out); CB_REGLOBAL(w.accept.path); CB_REGLOBAL(w.accept.len_ctx);
-  CB_REGLOBAL(w.accept.len_user); CB_REGLOBAL(w.accept.tok_user);
-#undef CB_REGLOBAL
+  CB_PIN(w.tickets); CB_PIN(w.accept.slot_stride); CB_PIN(w.accept.nchunks);
 }
 #undef CB_PIN
 
