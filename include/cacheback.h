@@ -219,6 +219,21 @@ int cb_last_launch_info(cb_ctx *ctx, int32_t info[4]);
  * `workgroups` (<= 1024) workgroups of the last launch to host memory, 8 values each. */
 int cb_debug_timestamps(cb_ctx *ctx, uint64_t *out, int32_t workgroups);
 
+/* Test hook for an assumption of the MFMA attention kernel, which covers loads to registers and
+ * LDS-DMA loads with counted waits of its own: that the two kinds are counted off the wave's
+ * vector-memory counter in the order they were requested.  Enqueues probe kernels on the stream
+ * (no context needed): `workgroups` x `iters` times a cold load of one kind followed by eight hot
+ * loads of the other, a wait that leaves at most those eight in flight, and an immediate look at
+ * what the cold load was to bring.  d_cold[i] must hold (uint32)i * 2654435761 + 12345 for
+ * i < cold_dwords, with cold_dwords >= workgroups * iters * 4096 + 256; d_hot >= 512 dwords of
+ * anything; d_result: 8 zeroed dwords, to which the kernels add the numbers of lane-reads that did
+ * not see the loaded value: [0]/[1] register load first, read early / after a full wait; [2]/[3]
+ * LDS-DMA first, early / full; [4]/[5] a control that reads the register without waiting (expected
+ * to be non-zero: it shows that a violated order would be seen).  All pointers are device memory.
+ * CB_EINVAL for bad arguments, CB_EHIP if a launch fails. */
+int cb_probe_load_order(void *hip_stream, const uint32_t *d_cold, int64_t cold_dwords, const uint32_t *d_hot,
+                        int64_t hot_dwords, int32_t workgroups, int32_t iters, uint32_t *d_result);
+
 const char *cb_last_error(const cb_ctx *ctx); /* "" when the last call succeeded; ctx may be NULL
                                                  for the error of a failed cb_init */
 void cb_destroy(cb_ctx *ctx);

@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import glob
 import os
+import re
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
 
@@ -26,11 +27,67 @@ def _compile(src: str) -> str:
     return obj
 
 
+def device_asm(src: str) -> str:
+    """The gfx950 assembly hipcc makes of one source file, with the library's flags."""
+    os.makedirs(OBJ, exist_ok=True)
+    out = os.path.join(OBJ, os.path.basename(src) + ".s")
+    flags = [f for f in FLAGS if f not in ("-fPIC",)]
+    subprocess.run(["hipcc", *flags, "-S", "--offload-device-only", src, "-o", out], check=True,
+                   stderr=subprocess.DEVNULL)
+    with open(out) as f:
+        return f.read()
+
+
+_REG = re.compile(r"\bv\[(\d+):(\d+)\]|\bv(\d+)\b")
+
+
+def untracked_load_violations(asm: str) -> list:
+    """The attention kernel issues some loads as inline assembly the compiler does not know to be
+    loads, and waits for them itself before their first use.  That is only right while the compiler
+    leaves the destination registers alone in between (a copy or a spill would read them before
+    the data is there).  For every such load (a global_load_dwordx4 inside an inline-assembly
+    block) this walks down the listing to the first instruction that names one of its registers
+    and reports the load if no vmcnt wait and no branch (where the walk cannot follow) came
+    before it.  Returns a list of (line number, text) pairs, empty if all is well."""
+    lines = asm.split("\n")
+    bad = []
+    in_asm = False
+    for i, line in enumerate(lines):
+        if "ASMSTART" in line:
+            in_asm = True
+            continue
+        if "ASMEND" in line:
+            in_asm = False
+            continue
+        m = re.search(r"global_load_dwordx4 v\[(\d+):(\d+)\]", line) if in_asm else None
+        if not m:
+            continue
+        lo, hi = int(m.group(1)), int(m.group(2))
+        covered = False
+        for j in range(i + 1, len(lines)):
+            code = lines[j].split(";")[0]
+            if "s_waitcnt vmcnt" in code or re.search(r"\bs_(c?branch|endpgm)", code):
+                covered = True
+                break
+            touched = False
+            for r in _REG.finditer(code):
+                a, b = (int(r.group(1)), int(r.group(2))) if r.group(1) else (int(r.group(3)),) * 2
+                touched |= a <= hi and b >= lo
+            if touched:
+                break
+        if not covered:
+            bad.append((i + 1, line.strip()))
+    return bad
+
+
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))
+    bad = untracked_load_violations(device_asm(os.path.join(CSRC, "cb_attn_mfma.hip")))
+    if bad:
+        raise RuntimeError(f"cb_attn_mfma.hip: registers of untracked loads are touched before their wait: {bad[:4]}")
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     if verbose:
         print(LIB)
