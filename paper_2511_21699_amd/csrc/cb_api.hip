@@ -97,6 +97,7 @@ struct cb_ctx {
   int32_t* h_path;
   int32_t* h_argmax;
   int32_t* h_misc;  // [0] status, [1..] new_len
+  int32_t* d_hblock = nullptr;  // the pinned block's address on the device
   void* h_block;
   // state of the last verify
   bool have_verify;
@@ -473,6 +474,14 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
     delete ctx;
     return set_err(nullptr, CB_EHIP, "hipHostMalloc: %s", hipGetErrorString(e));
   }
+  void* dptr = nullptr;
+  e = hipHostGetDevicePointer(&dptr, ctx->h_block, 0);
+  if (e != hipSuccess) {
+    (void)hipHostFree(ctx->h_block);
+    delete ctx;
+    return set_err(nullptr, CB_EHIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e));
+  }
+  ctx->d_hblock = static_cast<int32_t*>(dptr);
   int32_t* h = static_cast<int32_t*>(ctx->h_block);
   ctx->h_parent = h; h += mt;
   ctx->h_tokens = h; h += mt;
@@ -542,19 +551,20 @@ int cb_verify_tree(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int total = node_offsets[batch];
   const size_t stride = (size_t)ctx->cfg.max_depth + 1;
-  // one copy in (parents and tokens back to back), one copy out (lengths and tokens back to back)
+  // No copies: the kernels read the tree from, and write the results to, the context's pinned host
+  // block through its device address (a few hundred bytes each way; two staged copies cost more
+  // than the kernels' reads across the bus).  Parents and tokens back to back, lengths and tokens
+  // back to back.
   int32_t* h_tree = ctx->h_parent;
   memcpy(h_tree, tree_parent, (size_t)total * 4);
   memcpy(h_tree + total, draft_tokens, (size_t)total * 4);
-  int32_t* d_parent = ctx->dev<int32_t>(ctx->lay.parent);
+  int32_t* d_parent = ctx->d_hblock + (h_tree - static_cast<int32_t*>(ctx->h_block));
   int32_t* d_tokens = d_parent + total;
-  CB_HIP(ctx, hipMemcpyAsync(d_parent, h_tree, (size_t)total * 8, hipMemcpyHostToDevice, st));
-  int32_t* d_len = ctx->dev<int32_t>(ctx->lay.res_len);
+  int32_t* h_res = ctx->h_len;
+  int32_t* d_len = ctx->d_hblock + (h_res - static_cast<int32_t*>(ctx->h_block));
   int32_t* d_tok = d_len + batch;
   rc = run_pipeline(ctx, st, batch, q, kv, kv_len, node_offsets, d_parent, d_tokens, logits, attn_out, d_len, d_tok);
   if (rc) return rc;
-  int32_t* h_res = ctx->h_len;
-  CB_HIP(ctx, hipMemcpyAsync(h_res, d_len, (size_t)batch * (1 + stride) * 4, hipMemcpyDeviceToHost, st));
   CB_HIP(ctx, hipStreamSynchronize(st));
   memcpy(accepted_len, h_res, (size_t)batch * 4);
   memcpy(accepted_tokens, h_res + batch, (size_t)batch * stride * 4);
