@@ -6,11 +6,12 @@
 // MFMA contractions; the KV sequence is split across workgroups and the partial softmax states
 // (o, m, l) are merged afterwards.
 //
-// Work decomposition: one workgroup (4 wavefronts) per (sequence, kv head, 64*R-row tile, split).
-// Wave w owns 16*R rows and sweeps every key of the split, so its softmax state never has to be
-// combined with another wave's.  K/V tiles of 32 keys are brought straight from HBM into an
-// NS-deep LDS ring with global_load_lds (no registers held by loads in flight) and are shared by
-// the four waves.
+// Work decomposition: one workgroup (4 or 8 wavefronts, see attn_tile) per (sequence, kv head, row
+// tile, split).  A wave owns 16*R rows; K/V stages are brought straight from HBM into an NS-deep LDS
+// ring by LDS-DMA (global_load_lds: no registers held by loads in flight) and are shared by the
+// waves.  All loads of the sweep -- the ring's requests, the query rows, a logits item -- are issued
+// as instructions the compiler does not interpret and are covered by the kernel's own counted waits
+// (lds_dma_b128, load_b128_untracked).
 //
 // Register layouts (v_mfma_f32_16x16x32_bf16; lane l, c = l%16, kg = l/16):
 //   scores are computed transposed, S^T = K Q^T: A = K rows (key c of the sub-tile, dims
