@@ -225,6 +225,36 @@ def main():
     argmax_us = timed_stage(4)
     verify_us = timed_stage(15)          # attention + argmax + acceptance (no compaction): one launch when fused
     attn_gbps = attn_bytes / attn_us / 1e3
+
+    # ---- what this machine delivers for a bare streaming read of as many bytes as the attention
+    # sweeps: one launch of the library's read probe per cold buffer, replayed the same way
+    def timed_stream_read():
+        nb = (attn_bytes + 15) // 16 * 16
+        bufs = [torch.randint(0, 2 ** 31 - 1, (nb // 4,), dtype=torch.int32, device="cuda") for _ in range(copies)]
+        sink = torch.zeros(256, dtype=torch.int32, device="cuda")
+        reps = 20 if copies == 1 else 1
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            B.probe_stream_read(bufs[0], nb, sink, stream=side)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(reps):
+                    for b in bufs:
+                        B.probe_stream_read(b, nb, sink, stream=side)
+            for _ in range(3):
+                graph.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n = max(1, args.steps // (reps * copies))
+            side.synchronize()
+            e0.record(side)
+            for _ in range(n):
+                graph.replay()
+            e1.record(side)
+            e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (n * reps * copies)
+
+    stream_us = timed_stream_read()
+    stream_gbps = attn_bytes / stream_us / 1e3
     # The dominant kernel of the timed step.  Small calls run the whole verification as one launch
     # (k_verify_mfma): its algorithmic bytes are the attention's plus the logits'.  Otherwise it is
     # the attention kernel (with its split merge).
@@ -258,6 +288,9 @@ def main():
         "attention_us": round(attn_us, 3),
         "attention_gbps": round(attn_gbps, 1),
         "attention_pct_hbm_peak": round(100 * attn_gbps / HBM_PEAK_GBPS, 2),
+        "stream_read": {"what": "one launch of a bare read kernel over as many bytes, same cold rotation and replay",
+                        "us": round(stream_us, 3), "gbps": round(stream_gbps, 1),
+                        "attention_pct_of_it": round(100 * attn_gbps / stream_gbps, 1)},
         "argmax_us": round(argmax_us, 3),
         "verify_us": round(verify_us, 3),
         "one_launch_verify": info["fused"],

@@ -234,6 +234,12 @@ int cb_debug_timestamps(cb_ctx *ctx, uint64_t *out, int32_t workgroups);
 int cb_probe_load_order(void *hip_stream, const uint32_t *d_cold, int64_t cold_dwords, const uint32_t *d_hot,
                         int64_t hot_dwords, int32_t workgroups, int32_t iters, uint32_t *d_result);
 
+/* Measurement aid: enqueues a plain streaming read of `bytes` (a multiple of 16, 16-byte aligned)
+ * of device memory at d_src -- 1024 workgroups, 16-byte loads, nothing else -- so that a benchmark
+ * can time what this machine delivers for a bare read of the size the attention sweeps.  d_sink:
+ * 256 dwords of device memory (practically never written).  No context needed. */
+int cb_probe_stream_read(void *hip_stream, const void *d_src, int64_t bytes, uint32_t *d_sink);
+
 const char *cb_last_error(const cb_ctx *ctx); /* "" when the last call succeeded; ctx may be NULL
                                                  for the error of a failed cb_init */
 void cb_destroy(cb_ctx *ctx);

@@ -22,7 +22,7 @@ ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_E
 
 EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device", "cb_tree_attention_device",
            "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
-           "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_probe_load_order", "cb_last_error",
+           "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_probe_load_order", "cb_probe_stream_read", "cb_last_error",
            "cb_destroy"]
 
 
@@ -77,6 +77,7 @@ def load():
     L.cb_last_attention_ms.argtypes = [vp, C.POINTER(C.c_float)]
     L.cb_debug_timestamps.argtypes = [vp, C.POINTER(C.c_uint64), C.c_int32]
     L.cb_probe_load_order.argtypes = [vp, vp, C.c_int64, vp, C.c_int64, C.c_int32, C.c_int32, vp]
+    L.cb_probe_stream_read.argtypes = [vp, vp, C.c_int64, vp]
     L.cbd_table_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(vp)]
     L.cbd_table_destroy.argtypes = [vp]
     L.cbd_table_destroy.restype = None
@@ -153,6 +154,16 @@ def probe_load_order(d_cold, d_hot, workgroups: int, iters: int, d_result, strea
                                     C.c_void_p(d_result.data_ptr()))
     if rc:
         raise CbError(rc, "cb_probe_load_order rejected the arguments")
+
+
+def probe_stream_read(d_src, nbytes: int, d_sink, stream=None) -> None:
+    """Enqueue a bare streaming read of the first `nbytes` of the tensor d_src (cb_probe_stream_read)."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = load().cb_probe_stream_read(C.c_void_p(st.cuda_stream), C.c_void_p(d_src.data_ptr()), nbytes,
+                                     C.c_void_p(d_sink.data_ptr()))
+    if rc:
+        raise CbError(rc, "cb_probe_stream_read rejected the arguments")
 
 
 def workspace_bytes(cfg: CbConfig) -> int:
