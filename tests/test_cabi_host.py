@@ -137,3 +137,14 @@ def test_attention_plan_rejects_bad_shapes():
     for kv, offs in (([5], [1, 4]), ([5], [0, 0]), ([5], [0, 9]), ([-1], [0, 3]), ([1, 2, 3], [0, 1, 2, 3])):
         with pytest.raises(B.CbError):
             B.plan_attention(cfg, kv, offs)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only and says so (before it touches torch or the library)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
