@@ -519,7 +519,9 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   // Workgroups are handed to the 8 XCDs round-robin in dispatch order.  With xcd_remap the
   // dispatch index d is renumbered to j = (d % 8) * (T / 8) + d / 8, so that consecutive j --
   // in particular all splits of one (sequence, kv head, row tile) -- sit on the same XCD and
-  // meet in its L2.
+  // meet in its L2.  Tiles are numbered with the sequence running fastest: an XCD's share of the
+  // tiles (a contiguous range of j) then holds a few heads of every sequence rather than every
+  // head of a few sequences, so a batch of unequal lengths loads the XCDs equally.
   int split, by, b;
   {
     const int T = p.grid_x * p.grid_y * p.grid_z;
@@ -527,8 +529,8 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     const int j = p.xcd_remap ? (d & 7) * (T >> 3) + (d >> 3) : d;
     split = j % p.grid_x;
     const int rest = j / p.grid_x;
-    by = rest % p.grid_y;
-    b = rest / p.grid_y;
+    b = rest % p.grid_z;
+    by = rest / p.grid_z;
   }
   const int hk = by % p.Hkv, rt = by / p.Hkv;
   const int g = p.Hq / p.Hkv;
