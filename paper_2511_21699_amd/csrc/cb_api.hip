@@ -20,7 +20,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
   size_t anc, parent, tokens, amax_partial, amax_out, path, len_ctx, res_len, res_tok, new_len, status,
-      tickets, amax_tickets, amax_lines, dbg, partial, total;
+      tickets, coop_tickets, amax_tickets, amax_lines, dbg, partial, total;
   int amax_chunks;
   int max_total_nodes;
   int max_splits;
@@ -58,7 +58,7 @@ WsLayout ws_layout(const cb_config& c) {
   L.max_splits = effective_max_splits(c);
   L.amax_chunks = (int)(((int64_t)c.vocab_size + kArgmaxChunk - 1) / kArgmaxChunk);
   const int g = c.num_q_heads / c.num_kv_heads;
-  L.ticket_count = 2 * c.max_batch * c.num_kv_heads * ((c.max_nodes * g + kRowTile - 1) / kRowTile);  // one 64-bit ticket word per tile
+  L.ticket_count = 4 * c.max_batch * c.num_kv_heads * ((c.max_nodes * g + kRowTile - 1) / kRowTile);  // two 64-bit words per tile
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   L.anc = take(mt * kAncWords * 4);
@@ -73,6 +73,7 @@ WsLayout ws_layout(const cb_config& c) {
   L.new_len = take(c.max_batch * 4);
   L.status = take(4);
   L.tickets = take((size_t)L.ticket_count * 4);
+  L.coop_tickets = take((size_t)kCoopTiles * kCoopTicketStride);
   L.amax_tickets = take(CB_MAX_BATCH * 4);
   // argmax partials of the one-launch verification, one 128-byte line each (it takes sequences of at most 64 nodes)
   L.amax_lines = take((size_t)c.max_batch * std::min(c.max_nodes, 64) * L.amax_chunks * 128);
@@ -109,7 +110,7 @@ struct cb_ctx {
   int32_t last_len[CB_MAX_BATCH];
   hipStream_t last_stream;
   // options
-  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug, opt_fork, opt_fuse;
+  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug, opt_fork, opt_fuse, opt_coop, opt_spin;
   hipEvent_t ev0, ev1, ev_fork, ev_join;
   hipStream_t aux;  // second stream (default priority) for the logits scan beside the attention
   bool ev_valid;
@@ -255,6 +256,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.parent = d_parent;
   ap.partial = ctx->dev<float>(ctx->lay.partial);
   ap.tickets = ctx->dev<uint32_t>(ctx->lay.tickets);
+  ap.coop_tickets = ctx->dev<uint32_t>(ctx->lay.coop_tickets);
   ap.Hq = c.num_q_heads;
   ap.Hkv = c.num_kv_heads;
   ap.D = c.head_dim;
@@ -266,6 +268,8 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.dbg_ts = ctx->dev<unsigned long long>(ctx->lay.dbg);
   ap.debug_flags = (int32_t)ctx->opt_debug;
   ap.max_depth = c.max_depth;
+  ap.coop_merge = ctx->opt_coop ? 0 : -1;
+  ap.spin_limit = (int32_t)ctx->opt_spin;
 
   // bit 0 ancestor sets, 1 attention, 2 argmax, 3 acceptance; the option is a measurement aid, the
   // mask is what the entry point asks for (cb_tree_attention_device: the first two)
@@ -467,6 +471,8 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   ctx->ws = static_cast<char*>(workspace);
   ctx->opt_stages = 15;
   ctx->opt_fuse = 1;
+  ctx->opt_coop = 1;
+  ctx->opt_spin = 64;
   const size_t mt = lay.max_total_nodes, stride = (size_t)cfg->max_depth + 1;
   const size_t ints = mt * 3 + cfg->max_batch * (1 + 2 * stride) + 1 + cfg->max_batch;
   hipError_t e = hipHostMalloc(&ctx->h_block, ints * 4, hipHostMallocDefault);
@@ -497,6 +503,7 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipMemset(ctx->ws + lay.status, 0, 4);
   if (e == hipSuccess) e = hipMemset(ctx->ws + lay.tickets, 0, (size_t)lay.ticket_count * 4);
+  if (e == hipSuccess) e = hipMemset(ctx->ws + lay.coop_tickets, 0, (size_t)kCoopTiles * kCoopTicketStride);
   if (e == hipSuccess) e = hipMemset(ctx->ws + lay.amax_tickets, 0, CB_MAX_BATCH * 4);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
@@ -651,6 +658,8 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   else if (!strcmp(name, "debug_flags")) ctx->opt_debug = value;
   else if (!strcmp(name, "parallel_scan")) ctx->opt_fork = value;
   else if (!strcmp(name, "fuse_logits")) ctx->opt_fuse = value;
+  else if (!strcmp(name, "coop_merge")) ctx->opt_coop = value;
+  else if (!strcmp(name, "merge_spin_limit")) ctx->opt_spin = value < 0 ? 0 : (value > 4096 ? 4096 : value);
   else return set_err(ctx, CB_EINVAL, "unknown option '%s'", name);
   return CB_OK;
 }

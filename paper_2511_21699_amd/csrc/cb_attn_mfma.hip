@@ -396,9 +396,9 @@ __device__ __forceinline__ void compute_stage_pair(const uint4* __restrict__ ks,
 __device__ __forceinline__ void pin_args(AttnParams& p) {
   CB_PIN(p.q); CB_PIN(p.out); CB_PIN(p.kv.k); CB_PIN(p.kv.v); CB_PIN(p.kv.block_table);
   CB_PIN(p.kv.seq_stride); CB_PIN(p.kv.token_stride); CB_PIN(p.kv.head_stride); CB_PIN(p.kv.num_blocks);
-  CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.parent); CB_PIN(p.partial); CB_PIN(p.tickets);
+  CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.parent); CB_PIN(p.partial); CB_PIN(p.tickets); CB_PIN(p.coop_tickets);
   CB_PIN(p.Hq); CB_PIN(p.Hkv); CB_PIN(p.chunk); CB_PIN(p.nsplit); CB_PIN(p.batch); CB_PIN(p.scale);
-  CB_PIN(p.external_merge); CB_PIN(p.max_depth); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags);
+  CB_PIN(p.external_merge); CB_PIN(p.max_depth); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags); CB_PIN(p.coop_merge); CB_PIN(p.spin_limit);
   CB_PIN(p.status); CB_PIN(p.dbg_ts);
 }
 __device__ __forceinline__ void pin_logits_args(LogitsWork& w) {
@@ -415,11 +415,10 @@ __device__ __forceinline__ void pin_logits_args(LogitsWork& w) {
 // split 0's unit of the lane's rr-th row tile).  Splits are combined online, BS per batch with all
 // of a batch's loads in flight together: m = max m_t, w_t = e^(m_t - m),
 // o = sum w_t o_t / sum w_t l_t.  POL is the buffer cache policy of the loads.
-template <int R, int NDT, int POL>
+template <int R, int NDT, int POL, int BS = 32 / NDT>
 __device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const int64_t* grow, const uint32_t* ubyte,
                                            CB_GLOBAL uint16_t* gout, int nsplit_b, int dt0, int l) {
-  constexpr int D = 128;
-  constexpr int BS = 32 / NDT;  // splits per batch
+  constexpr int D = 128;  // (BS: splits per batch)
   const int kg = l >> 4, c = l & 15;
 #pragma unroll
   for (int rr = 0; rr < R; rr++) {
@@ -512,6 +511,10 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   __shared__ int bt_lds[kMaxBtLds];
   __shared__ AncScratch anc_sh;  // ancestor sets of the whole tree, built here by the splits that reach the tree
   __shared__ int last_flag;
+  __shared__ int merge_flag;                 // cooperative merge: thread 64's verdict (0 = not yet)
+  __shared__ unsigned long long merge_todo;  // ... and the slices this workgroup merges
+  __shared__ int merge_flag2;                // second verdict: slices of workgroups that gave up (completing workgroup only)
+  __shared__ unsigned long long merge_todo2;
   constexpr int D = 128;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
   const int gi = w >> 2, wi = w & 3;
@@ -541,6 +544,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   // and wait for all of them wherever it needs one)
   CB_LDS unsigned long long* ts = (CB_LDS unsigned long long*)ts_sh;
   const bool do_ts = (p.debug_flags & 32) && threadIdx.x == 0 && wg_linear < 1024;
+  const bool do_ts64 = (p.debug_flags & 32) && threadIdx.x == 64 && wg_linear < 1024;
 #define CB_TS(i) do { if (do_ts) ts[i] = wall_clock64(); } while (0)
   if (do_ts) {
 #pragma unroll
@@ -615,7 +619,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   }
 
   const float c2 = p.scale * 1.4426950408889634f;  // softmax scale in the log2 domain
-  const int last_key = len - 1;
+  const int last_key = k1 - 1;  // requests past the split's end repeat its last row (never used; the next split reads its own keys)
 
 #define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * SK, last_key, w, l)
   const bool fine_ts = (p.debug_flags & 1024) != 0;  // (timing aid: slots 5-7 stamp the issue phase instead)
@@ -805,56 +809,160 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   if constexpr (kHookEarly) hook->stamp(4);
   if (nsplit_b == 1 || p.external_merge) return;  // (a following kernel merges: the kernel boundary orders the stores)
 
-  // ---- split merge by the last workgroup of this (sequence, kv head, row tile) to finish.
-  // The partials above are write-through stores; once they have completed (vmcnt 0) the workgroup
-  // takes a ticket with a device-scope atomic.  The workgroup that draws the last ticket reads all
-  // partials of the tile.  No cache-wide write-back or invalidate is involved (a __threadfence()
-  // per workgroup costs a full L2 sweep on this chip).
+  // ---- split merge.  The partials above are write-through stores; once they have completed
+  // (vmcnt 0) the workgroup takes a ticket with a device-scope atomic.  No cache-wide write-back or
+  // invalidate is involved (a __threadfence() per workgroup costs a full L2 sweep on this chip).
+  //
+  // Ticket word of a tile (64 bits, zero between launches): arrivals in bits 0-11 and, to learn
+  // whether every split ran on one XCD, the sum (bits 24-39) and the sum of squares (bits 40-59)
+  // of the arrivals' XCC_ID (hardware register 20, bits 3:0): all ids equal mine  <=>
+  // sum = n*id and sumsq = n*id*id.  A second word per tile holds one bit per split whose
+  // workgroup gave up waiting (cooperative merge only).
+  if (tid == 64) { merge_flag = 0; merge_flag2 = 0; }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   CB_TS(5);
-  if (p.debug_flags & 1) return;
   const int tiles = p.grid_y / p.Hkv;
-  CB_GLOBAL unsigned long long* ticket =
-      (CB_GLOBAL unsigned long long*)p.tickets + (((int64_t)b * p.Hkv + hk) * tiles + rt);
-  if (tid == 0) {
-    // One 64-bit atomic carries the arrival count (bits 0-15) and, to learn whether every split ran
-    // on this XCD, the sum (bits 16-35) and sum of squares (bits 36-59) of the arrivals' XCC_ID
-    // (hardware register 20, bits 3:0): all ids equal mine  <=>  sum = n*id and sumsq = n*id*id.
-    const unsigned long long x = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
-    const unsigned long long mine = 1ull | (x << 16) | ((x * x) << 36);
-    uint32_t scan_old = 0;
-    if constexpr (kHookEarly) scan_old = hook->ticket_first_issue();
-    const unsigned long long tot = __hip_atomic_fetch_add(ticket, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
-    const unsigned long long n = tot & 0xffffull;
-    int flag = (n == (unsigned long long)nsplit_b) ? 1 : 0;
-    if (flag) {
-      const unsigned long long sum = (tot >> 16) & 0xfffffull, sumsq = tot >> 36;
-      if (sum != n * x || sumsq != n * x * x) {
-        flag = 2;  // some split ran on another XCD: its partials are not in this L2
-        __hip_atomic_fetch_or((CB_GLOBAL int32_t*)p.status, 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // (cooperative merge: the tiles' words are polled, so each tile has a 4 KiB stretch of its own
+  // in a separate area -- neighbours in one line would all be served by one memory channel)
+  const int64_t tile_id = ((int64_t)b * p.Hkv + hk) * tiles + rt;
+  CB_GLOBAL unsigned long long* ticket = p.coop_merge ? (CB_GLOBAL unsigned long long*)p.coop_tickets + tile_id * (kCoopTicketStride / 8)
+                                                      : (CB_GLOBAL unsigned long long*)p.tickets + 2 * tile_id;
+  constexpr unsigned long long kArrivals = 0xfffull;
+  const unsigned long long xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
+  const unsigned long long arrive = 1ull | (xcc << 24) | ((xcc * xcc) << 40);
+  auto one_xcd = [&](unsigned long long tot) {
+    const unsigned long long n = tot & kArrivals, sum = (tot >> 24) & 0xffffull, sumsq = tot >> 40;
+    return sum == n * xcc && sumsq == n * xcc * xcc;
+  };
+
+  if (!p.coop_merge) {
+    // Merge by the last workgroup of the tile to arrive: the others leave at once and free their
+    // compute units (grids of several rounds of workgroups).
+    if (tid == 0) {
+      uint32_t scan_old = 0;
+      if constexpr (kHookEarly) scan_old = hook->ticket_first_issue();
+      const unsigned long long tot = __hip_atomic_fetch_add(ticket, arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + arrive;
+      int flag = ((tot & kArrivals) == (unsigned long long)nsplit_b) ? 1 : 0;
+      if (flag) {
+        if (!one_xcd(tot)) {
+          flag = 2;  // some split ran on another XCD: its partials are not in this L2
+          __hip_atomic_fetch_or((CB_GLOBAL int32_t*)p.status, 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
       }
-      __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+      last_flag = flag;
+      if constexpr (kHookEarly) hook->ticket_first_resolve(scan_old);
     }
-    last_flag = flag;
-    if constexpr (kHookEarly) hook->ticket_first_resolve(scan_old);
+    __syncthreads();
+    CB_TS(6);
+    // If this workgroup completed the logits scan, its first wave runs the acceptance now, while the
+    // other waves go straight on to the merge below.
+    if constexpr (kHookEarly) {
+      hook->first_counted();
+      hook->accept_first();
+      hook->stamp(5);
+    }
+    if (!last_flag) return;
+    // Same XCD: the write-through stores left the lines in this L2, plain (cached) loads are coherent
+    // with them.  Otherwise read past the L2 with agent-coherent loads.
+    if (last_flag == 1) merge_tile<R, ndt, 0>(prsrc, grow, ubyte, gout, nsplit_b, dt0, l);
+    else merge_tile<R, ndt, kAgentCoherent>(prsrc, grow, ubyte, gout, nsplit_b, dt0, l);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    CB_TS(7);
+    return;
   }
-  __syncthreads();
-  CB_TS(6);
-  // If this workgroup completed the logits scan, its first wave runs the acceptance now, while the
-  // other waves go straight on to the merge below.
+
+  // ---- cooperative merge (the whole grid is resident at once: one round of workgroups).  Every
+  // workgroup of the tile merges a slice of it -- the (16-row tile, dim tile) units u with
+  // u % nsplit_b == split -- once all splits have arrived, so no compute unit has to pull the whole
+  // tile's partials through its own memory pipe.  Thread 64 arrives and then polls the ticket, at
+  // most spin_limit times: the tile is complete when the arrivals equal nsplit_b, or when the word
+  // is zero again (the completing workgroup zeroes it for the next launch; after one's own arrival
+  // it cannot be zero for any other reason).  A workgroup that gives up sets its bit in the tile's
+  // second word, looks at the ticket once more and leaves if the tile is still incomplete: the
+  // completing workgroup reads that word after its own arrival, so it finds the bit and merges the
+  // slice.  (If the last look shows the tile complete after all, the workgroup merges its slice
+  // itself: the completing workgroup may have read the word before the bit was there.  If both
+  // merge it they write the same bytes.)  Wave 0 is not waited for by anyone: in the one-launch
+  // verification it draws the logits ticket and may have to run the acceptance first.
+  CB_GLOBAL unsigned long long* gave_up = ticket + 1;
   if constexpr (kHookEarly) {
+    if (tid == 0) hook->ticket_first_resolve(hook->ticket_first_issue());
     hook->first_counted();
     hook->accept_first();
     hook->stamp(5);
   }
-  if (!last_flag) return;
-  // Same XCD: the write-through stores left the lines in this L2, plain (cached) loads are coherent
-  // with them.  Otherwise read past the L2 with agent-coherent loads.
-  if (last_flag == 1) merge_tile<R, ndt, 0>(prsrc, grow, ubyte, gout, nsplit_b, dt0, l);
-  else merge_tile<R, ndt, kAgentCoherent>(prsrc, grow, ubyte, gout, nsplit_b, dt0, l);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  CB_TS(7);
+  bool reset_late = false;
+  if (tid == 64) {
+    unsigned long long tot = __hip_atomic_fetch_add(ticket, arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + arrive;
+    const bool completes = (tot & kArrivals) == (unsigned long long)nsplit_b;
+    auto complete = [&](unsigned long long t) { return (t & kArrivals) == (unsigned long long)nsplit_b || t == 0ull; };
+    for (int spin = 0; !complete(tot) && spin < p.spin_limit; spin++) {
+      __builtin_amdgcn_s_sleep(2);
+      tot = __hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    unsigned long long todo = 1ull << split, todo2 = 0;
+    bool own_bit = false;
+    if (!complete(tot)) {
+      // (the returning form: the bit is in memory before the ticket is looked at again)
+      const unsigned long long before = __hip_atomic_fetch_or(gave_up, 1ull << split, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      asm volatile("s_waitcnt vmcnt(0)" ::"v"(before) : "memory");
+      tot = __hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      own_bit = true;
+      if (!complete(tot)) todo = 0;
+      __hip_atomic_fetch_or((CB_GLOBAL int32_t*)p.status, 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // plain loads only when the ticket itself says that every split ran on this XCD
+    int flag = (tot != 0ull && one_xcd(tot)) ? 1 : 2;
+    if (todo != 0 && flag == 2) __hip_atomic_fetch_or((CB_GLOBAL int32_t*)p.status, 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    merge_todo = todo;
+    __hip_atomic_store(&merge_flag, flag, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (do_ts64) ts[6] = wall_clock64();
+    if (completes) {
+      todo2 = __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~todo;
+      if (todo2 != 0) __hip_atomic_store(gave_up, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (!(p.debug_flags & 2048)) __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+      else reset_late = true;
+    } else if (own_bit && todo != 0) {
+      __hip_atomic_fetch_and(gave_up, ~(1ull << split), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    merge_todo2 = todo2;
+    __hip_atomic_store(&merge_flag2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  // the waves wait for thread 64's verdicts in LDS (no barrier: wave 0 may still be busy)
+  int flag;
+  while ((flag = __hip_atomic_load(&merge_flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP)) == 0) __builtin_amdgcn_s_sleep(1);
+  int k = 0;  // running number of this workgroup's units: unit k goes to wave (k + 1) % NW
+  auto merge_slices = [&](unsigned long long todo) {
+    constexpr int NW = NT / 64;
+    constexpr int NU = (RT / 16) * 8;  // units of the workgroup's tile
+    for (int s2 = 0; s2 < nsplit_b; s2++) {
+      if (!((todo >> s2) & 1ull)) continue;
+      for (int u = s2; u < NU; u += nsplit_b, k++) {
+        if ((k + 1) % NW != w) continue;
+        const int tl = u >> 3, dt = u & 7;
+        const int row = row0 + tl * 16 + c;
+        if (row - c >= M) continue;
+        const int node = row / g, hg = row - node * g;
+        int64_t gr1[1] = {row < M ? (int64_t)(off + node) * p.Hq + hk * g + hg : -1};
+        uint32_t ub1[1] = {(uint32_t)(hk * ((M + 15) >> 4) + (row0 >> 4) + tl) * (uint32_t)p.nsplit * (uint32_t)kUnitBytes};
+        if (flag == 1) merge_tile<1, 1, 0, 8>(prsrc, gr1, ub1, gout, nsplit_b, dt, l);
+        else merge_tile<1, 1, kAgentCoherent, 8>(prsrc, gr1, ub1, gout, nsplit_b, dt, l);
+      }
+    }
+  };
+  merge_slices(merge_todo);
+  while (__hip_atomic_load(&merge_flag2, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) __builtin_amdgcn_s_sleep(1);
+  if (merge_todo2 != 0) merge_slices(merge_todo2);
+  if (reset_late) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (do_ts64) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    ts[7] = wall_clock64();
+  }
 #undef CB_TS
 }
 
@@ -862,6 +970,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 // attention's eight to row wg, the logits hook's eight to row wg + 512.
 __device__ __forceinline__ void flush_timestamps(const AttnParams& p, const unsigned long long* ts_sh, bool hook_rows) {
   const int wg = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
+  if (p.debug_flags & 32) __syncthreads();  // (thread 64 stamps too)
   if (!(p.debug_flags & 32) || threadIdx.x != 0 || wg >= 1024) return;
   const CB_LDS unsigned long long* ts = (const CB_LDS unsigned long long*)ts_sh;
   CB_GLOBAL unsigned long long* out = (CB_GLOBAL unsigned long long*)p.dbg_ts;
@@ -1026,7 +1135,19 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   // one workgroup can pull about 50 GB/s of partials through its compute unit: beyond a few hundred
   // KiB per tile a separate, fully parallel merge kernel is cheaper than the in-kernel merge
   q.external_merge = (p.nsplit > 1 && (int64_t)p.nsplit * (rt_rows / 16) * kUnitBytes > 320 * 1024) ? 1 : 0;
-  if (p.debug_flags & 256) q.external_merge = 1;  // (timing aid)
+  // A grid that is resident in one round (one workgroup per compute unit) merges cooperatively:
+  // every workgroup of a tile takes a slice, so the volume per compute unit does not grow with
+  // the split count and no second launch is needed.
+  static int compute_units = 0;
+  if (compute_units == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) compute_units = n;
+    else compute_units = -1;
+  }
+  q.coop_merge = (p.coop_merge >= 0 && p.coop_tickets && p.nsplit > 1 && p.nsplit <= 64 && compute_units > 0 && T <= compute_units &&
+                  (int64_t)p.Hkv * tiles * p.batch <= kCoopTiles) ? 1 : 0;
+  if (q.coop_merge) q.external_merge = 0;
+  if (p.debug_flags & 256) { q.external_merge = 1; q.coop_merge = 0; }  // (timing aid)
   if (logits_work) {
     const LogitsWork& lw = *logits_work;
     if (!attn_mfma_can_fuse(p, max_nodes_in_call, (int64_t)lw.rows * lw.accept.nchunks, CB_BF16)) return hipErrorInvalidValue;

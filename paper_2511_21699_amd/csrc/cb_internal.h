@@ -9,6 +9,8 @@ namespace cb {
 constexpr int kAncWords = CB_MAX_NODES / 32;  // 256-bit ancestor set per node
 constexpr int kArgmaxChunk = 8192;            // logits elements scanned by one workgroup
 constexpr int kRowTile = 64;                  // query rows per workgroup in the MFMA attention
+constexpr int kCoopTiles = 512;               // tiles a cooperative split merge can serve (it needs the grid resident at once)
+constexpr int kCoopTicketStride = 4096;       // bytes between their ticket words
 // floats per (row, split) partial softmax state: o[D] unnormalised, m, l, padded to 16 bytes
 constexpr int partial_stride(int D) { return D + 4; }
 
@@ -152,7 +154,8 @@ struct AttnParams {
   const int32_t* parent;  // [sumN] device tree, local parent indices
   float* partial;       // split partials; scalar kernel: [sumN*Hq][nsplit][partial_stride(D)]: o[D] (unnormalised), m, l, pad;
                         // the MFMA kernel has its own bf16 layout (cb_attn_mfma.hip)
-  uint32_t* tickets;    // one 64-bit ticket word per (sequence, kv head, row tile)
+  uint32_t* tickets;    // two 64-bit words per (sequence, kv head, row tile): ticket, splits that gave up waiting
+  uint32_t* coop_tickets;  // cooperative merge: kCoopTiles stretches of kCoopTicketStride bytes, two 64-bit words used in each
   int32_t Hq, Hkv, D;
   int32_t chunk;        // keys per split
   int32_t nsplit;       // partial slots per row (>= splits any sequence uses)
@@ -161,6 +164,9 @@ struct AttnParams {
   int32_t xcd_remap;    // 1: renumber workgroups so that all splits of a tile run on one XCD
   int32_t grid_x, grid_y, grid_z;  // launch grid, repeated here so the kernel reads one argument block
   int32_t external_merge;  // 1: the kernel only writes partials; launch_attn_mfma runs a merge kernel afterwards
+  int32_t coop_merge;      // 1: every workgroup of a tile merges a slice of it after a bounded wait for the others
+                           // (set by the launcher when the grid is resident in one round); -1 on input: never
+  int32_t spin_limit;      // cooperative merge: polls of the tile's ticket before a workgroup gives up
   int32_t max_depth;    // deepest node the configuration allows (bounds the ancestor-set rounds)
   int32_t debug_flags;  // bit 0: skip the split merge (timing aid; output then undefined)
   int32_t* status;      // device status word (bit 4: a merge had to use cross-XCD loads)
