@@ -196,6 +196,15 @@ Plan plan_attention(const cb_config& c, int max_splits, int opt_impl, int opt_sp
     // should come out just under a whole number of rounds of 256 workgroups.  Take the fewest
     // splits that fill >= 85% of the machine in whole rounds (fewer splits = fewer partials).
     // efficiency of ns splits: keys swept / (256 units x whole rounds x keys of a full split)
+    auto workgroups = [&](int ns) {
+      const int chunk = ((p.max_len + ns - 1) / ns + 31) / 32 * 32;
+      int64_t t = 0;
+      for (int b = 0; b < batch; b++) {
+        const int n = node_offsets[b + 1] - node_offsets[b];
+        t += (int64_t)((n * g + rows_per_wg - 1) / rows_per_wg) * c.num_kv_heads * ((kv_len[b] + n + chunk - 1) / chunk);
+      }
+      return t;
+    };
     auto efficiency = [&](int ns) {
       const int chunk = ((p.max_len + ns - 1) / ns + 31) / 32 * 32;
       int64_t t = 0, keys = 0;
@@ -215,6 +224,14 @@ Plan plan_attention(const cb_config& c, int max_splits, int opt_impl, int opt_sp
       const double eff = efficiency(ns);
       if (eff >= 0.85) { nsplit = ns; best = eff; break; }
       if (eff > best) { best = eff; nsplit = ns; }
+    }
+    // A grid of one round merges cooperatively (no workgroup pulls a whole tile's partials), so
+    // there more splits cost next to nothing: take the best-filling count among the one-round ones.
+    if (best >= 0.85 && workgroups(nsplit) <= 256) {
+      for (int ns = nsplit + 1; ns <= cap && ns <= 64 && workgroups(ns) <= 256; ns++) {
+        const double eff = efficiency(ns);
+        if (eff > best + 1e-9) { best = eff; nsplit = ns; }
+      }
     }
   }
   nsplit = std::max(1, std::min(nsplit, max_splits));
@@ -472,7 +489,7 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   ctx->opt_stages = 15;
   ctx->opt_fuse = 1;
   ctx->opt_coop = 1;
-  ctx->opt_spin = 64;
+  ctx->opt_spin = 256;
   const size_t mt = lay.max_total_nodes, stride = (size_t)cfg->max_depth + 1;
   const size_t ints = mt * 3 + cfg->max_batch * (1 + 2 * stride) + 1 + cfg->max_batch;
   hipError_t e = hipHostMalloc(&ctx->h_block, ints * 4, hipHostMallocDefault);

@@ -7,7 +7,7 @@
 // (o, m, l) are merged afterwards.
 //
 // Work decomposition: one workgroup (4 or 8 wavefronts, see attn_tile) per (sequence, kv head, row
-// tile, split).  A wave owns 16*R rows; K/V stages are brought straight from HBM into an NS-deep LDS
+// tile, split).  A wave owns 16*R rows; K/V stages are brought straight from HBM into an LDS
 // ring by LDS-DMA (global_load_lds: no registers held by loads in flight) and are shared by the
 // waves.  All loads of the sweep -- the ring's requests, the query rows, a logits item -- are issued
 // as instructions the compiler does not interpret and are covered by the kernel's own counted waits
@@ -37,9 +37,10 @@ typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned uintx2;
 #define CB_LDS __attribute__((address_space(3)))
 constexpr int kAgentCoherent = 16;  // buffer cache policy: sc1 = coherent at agent (device) scope
 
-constexpr int kStageKeys = 32;                 // keys per LDS stage and wave group
-constexpr int kStageVecs = kStageKeys * 16;    // 16-byte pieces per K (or V) stage: 32 rows x 256 B
-constexpr int NS = 4;                          // ring depth: NS-1 stages in flight
+constexpr int kStageKeys = 32;                 // keys per half-stage: the unit of the LDS ring, one wave group's share of a stage
+constexpr int kStageVecs = kStageKeys * 16;    // 16-byte pieces per K (or V) half-stage: 32 rows x 256 B
+constexpr int NH = 9;                          // ring depth in half-stages (16 KiB each): 288 keys
+constexpr int PRO = 6;                         // half-stages requested before the first wait; the rest of the ring right after it
 constexpr int kMaxBtLds = 1024;                // block-table entries staged in LDS per split
 // Partial softmax state in this kernel's own format, one unit per (16-row tile, split), laid out in
 // the order the MFMA accumulators hold it: for each of the 8 dim tiles dt, lane (kg, c) of the wave
@@ -123,25 +124,22 @@ __device__ __forceinline__ void lds_dma_b128(const CB_GLOBAL char* src, CB_LDS u
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory");
 }
 
-// Wave `w` brings rows 8w..8w+7 of stage `s` (keys key0..key0+31) into the ring slot: two 1 KiB
-// loads for K and two for V.  LDS position of a 16-byte piece is fixed by the lane (row*16 + c);
-// which piece of the row lands there is chosen by the XOR swizzle so that the MFMA operand reads
-// below are free of bank conflicts.  Keys past the end are clamped to the last valid one (they
-// are masked in the softmax), so every address stays inside the cache.
-__device__ __forceinline__ void issue_stage(uint4* kdst, uint4* vdst, const KeyAddr& ka, const CB_GLOBAL char* kbase,
-                                            const CB_GLOBAL char* vbase, int key0, int last_key, int w, int l) {
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    const int r = 8 * w + 4 * i + (l >> 4);
-    const int c = l & 15;
-    int key = key0 + r;
-    key = key > last_key ? last_key : key;
-    const int64_t off = ka.byte_off(key);
-    const int pk = c ^ (r & 15);
-    const int pv = c ^ ((r & 7) << 1);
-    lds_dma_b128(kbase + off + pk * 16, (CB_LDS uint4*)kdst + (8 * w + 4 * i) * 16);
-    lds_dma_b128(vbase + off + pv * 16, (CB_LDS uint4*)vdst + (8 * w + 4 * i) * 16);
-  }
+// Wave `w` (of 8) brings rows 4w..4w+3 of a half-stage (keys key0..key0+31) into its ring slot: one
+// 1 KiB request for K and one for V.  LDS position of a 16-byte piece is fixed by the lane
+// (row*16 + c); which piece of the row lands there is chosen by the XOR swizzle so that the MFMA
+// operand reads below are free of bank conflicts.  Keys past `last_key` repeat it (they are never
+// used), so every address stays inside the split's own range.
+__device__ __forceinline__ void issue_half(uint4* kdst, uint4* vdst, const KeyAddr& ka, const CB_GLOBAL char* kbase,
+                                           const CB_GLOBAL char* vbase, int key0, int last_key, int w, int l) {
+  const int r = 4 * w + (l >> 4);
+  const int c = l & 15;
+  int key = key0 + r;
+  key = key > last_key ? last_key : key;
+  const int64_t off = ka.byte_off(key);
+  const int pk = c ^ (r & 15);
+  const int pv = c ^ ((r & 7) << 1);
+  lds_dma_b128(kbase + off + pk * 16, (CB_LDS uint4*)kdst + (4 * w) * 16);
+  lds_dma_b128(vbase + off + pv * 16, (CB_LDS uint4*)vdst + (4 * w) * 16);
 }
 
 template <int R>
@@ -412,13 +410,15 @@ __device__ __forceinline__ void pin_logits_args(LogitsWork& w) {
 // Split merge of one tile by the waves that swept it: every lane merges the elements it held --
 // its query row, dims 16 dt + 4 kg + {0..3} of NDT dim tiles from dt0 -- which is also how the
 // partials are laid out, so each load of a wave is 512 contiguous bytes (ubyte[rr]: byte offset of
-// split 0's unit of the lane's rr-th row tile).  Splits are combined online, BS per batch with all
-// of a batch's loads in flight together: m = max m_t, w_t = e^(m_t - m),
-// o = sum w_t o_t / sum w_t l_t.  POL is the buffer cache policy of the loads.
+// slot 0's unit of the lane's rr-th row tile).  Slots are combined online, BS per batch with all
+// of a batch's loads in flight together: m = max m_t, w_t = 2^(m_t - m),
+// o = sum w_t o_t / sum w_t l_t (m_t is stored in log2 units).  POL is the buffer cache policy of
+// the loads.  A slot that saw no visible key carries m_t = -inf, l_t = 0 and gets weight 0; the
+// reference is kept finite so that (-inf) - (-inf) never occurs.
 template <int R, int NDT, int POL, int BS = 32 / NDT>
 __device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const int64_t* grow, const uint32_t* ubyte,
-                                           CB_GLOBAL uint16_t* gout, int nsplit_b, int dt0, int l) {
-  constexpr int D = 128;  // (BS: splits per batch)
+                                           CB_GLOBAL uint16_t* gout, int nslots, int dt0, int l) {
+  constexpr int D = 128;
   const int kg = l >> 4, c = l & 15;
 #pragma unroll
   for (int rr = 0; rr < R; rr++) {
@@ -426,33 +426,38 @@ __device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const i
     floatx4 acc[NDT];
 #pragma unroll
     for (int i = 0; i < NDT; i++) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float lsum = 0.f, m_run = -INFINITY;
-    for (int t0 = 0; t0 < nsplit_b; t0 += BS) {
+    float lsum = 0.f, m_run = -3.0e38f;
+    // (the slot's offset is the same in all lanes: it travels as the load's scalar offset, so a
+    // load costs no vector arithmetic)
+    const uint32_t vo_ml = ubyte[rr] + kUnitMl + c * 8, vo_v = ubyte[rr] + dt0 * 512 + l * 8;
+    for (int t0 = 0; t0 < nslots; t0 += BS) {
       uintx2 v[BS][NDT];
       uintx2 ml[BS];
 #pragma unroll
       for (int u = 0; u < BS; u++) {
-        const int t = (t0 + u < nsplit_b) ? t0 + u : nsplit_b - 1;
-        const uint32_t tb = ubyte[rr] + t * kUnitBytes;
-        ml[u] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + kUnitMl + c * 8, 0, POL);
+        const int t = (t0 + u < nslots) ? t0 + u : nslots - 1;  // (a repeated slot: weight 0 below)
+        ml[u] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, vo_ml, t * kUnitBytes, POL);
 #pragma unroll
         for (int i = 0; i < NDT; i++)
-          v[u][i] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, tb + (dt0 + i) * 512 + l * 8, 0, POL);
+          v[u][i] = __builtin_amdgcn_raw_buffer_load_b64(prsrc, vo_v + i * 512, t * kUnitBytes, POL);
       }
-      float mb = -INFINITY;
+      // (all of the batch's loads are requested before anything looks at a result: left alone, the
+      // scheduler moves the first maxima up between the loads, and each then waits a round trip)
+      __builtin_amdgcn_sched_barrier(0);
+      float m_new = m_run;
 #pragma unroll
-      for (int u = 0; u < BS; u++)
-        if (t0 + u < nsplit_b) mb = fmaxf(mb, __uint_as_float(ml[u][0]));
-      const float m_new = fmaxf(m_run, mb);
-      const float resc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+      for (int u = 0; u < BS; u++) m_new = fmaxf(m_new, __uint_as_float(ml[u][0]));
+      if (t0 > 0) {  // (uniform)
+        const float resc = __builtin_amdgcn_exp2f(m_run - m_new);
 #pragma unroll
-      for (int i = 0; i < NDT; i++) acc[i] *= resc;
-      lsum *= resc;
+        for (int i = 0; i < NDT; i++) acc[i] *= resc;
+        lsum *= resc;
+      }
       m_run = m_new;
 #pragma unroll
       for (int u = 0; u < BS; u++) {
-        const float mt = __uint_as_float(ml[u][0]);
-        const float wgt = (t0 + u < nsplit_b && mt != -INFINITY) ? __expf(mt - m_new) : 0.f;
+        float wgt = __builtin_amdgcn_exp2f(__uint_as_float(ml[u][0]) - m_new);
+        wgt = (t0 + u < nslots) ? wgt : 0.f;
         lsum = fmaf(__uint_as_float(ml[u][1]), wgt, lsum);
 #pragma unroll
         for (int i = 0; i < NDT; i++) {
@@ -463,7 +468,7 @@ __device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const i
         }
       }
     }
-    const float inv = 1.0f / lsum;
+    const float inv = __builtin_amdgcn_rcpf(lsum);
     CB_GLOBAL uint16_t* orow = gout + grow[rr] * D;
 #pragma unroll
     for (int i = 0; i < NDT; i++) {
@@ -504,10 +509,11 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   const CB_GLOBAL int32_t* gbt = (const CB_GLOBAL int32_t*)p.kv.block_table;
   const CB_GLOBAL int32_t* gparent = (const CB_GLOBAL int32_t*)p.parent;
   constexpr int NT = 256 * G;
-  constexpr int SK = kStageKeys * G;  // keys per stage
-  constexpr int SV = kStageVecs * G;  // 16-byte pieces of K (or V) per stage
-  __shared__ uint4 K0[SV], K1[SV], K2[SV], K3[SV];  // one object per ring slot: the compiler tracks
-  __shared__ uint4 V0[SV], V1[SV], V2[SV], V3[SV];  // LDS-DMA completion per object
+  static_assert(G == 2, "the ring's requests are shared out among eight waves");
+  constexpr int SK = kStageKeys * G;  // keys per stage: two half-stages
+  // The ring: NH half-stage slots, each 8 KiB of K followed by 8 KiB of V; half-stage h of the
+  // split (keys k0 + 32 h ..) lives in slot h % NH.
+  __shared__ uint4 ring[NH * 2 * kStageVecs];
   __shared__ int bt_lds[kMaxBtLds];
   __shared__ AncScratch anc_sh;  // ancestor sets of the whole tree, built here by the splits that reach the tree
   __shared__ int last_flag;
@@ -535,7 +541,9 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     b = rest % p.grid_z;
     by = rest / p.grid_z;
   }
-  const int hk = by % p.Hkv, rt = by / p.Hkv;
+  // (row tiles of one kv head are neighbours in j: they sweep the same K/V and then share an XCD's L2)
+  const int tiles = p.grid_y / p.Hkv;
+  const int rt = by % tiles, hk = by / tiles;
   const int g = p.Hq / p.Hkv;
   const SeqShape shp = seq_shape(ml, b);
   const int wg_linear = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
@@ -584,7 +592,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   // overlaps with the prologue's own first-data latency, and the first stage's wait covers them.
   if constexpr (kHookEarly) hook->prefetch_first();
   // Everything this workgroup needs from memory is requested up front, oldest first: the query rows
-  // and ancestor words (to registers), then NS-1 stages of K/V (to LDS).
+  // and ancestor words (to registers), then the whole ring of K/V half-stages (to LDS).
   WaveState<R> st;
   int row_node[R];    // tree node of the lane's query (indexes the ancestor sets)
   int64_t grow[R];    // global output row (node * Hq + head), or -1 past the end
@@ -621,24 +629,32 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   const float c2 = p.scale * 1.4426950408889634f;  // softmax scale in the log2 domain
   const int last_key = k1 - 1;  // requests past the split's end repeat its last row (never used; the next split reads its own keys)
 
-#define CB_ISSUE(J, s) issue_stage(K##J, V##J, ka, kbase, vbase, k0 + (s) * SK, last_key, w, l)
+  const int nh = (k1 - k0 + kStageKeys - 1) / kStageKeys;  // half-stages of this split
+  const int nhw = nh < NH ? NH : nh;                       // half-stages requested
+  auto issue = [&](int h, int slot) {
+    uint4* const base = ring + slot * (2 * kStageVecs);
+    issue_half(base, base + kStageVecs, ka, kbase, vbase, k0 + h * kStageKeys, last_key, w, l);
+  };
   const bool fine_ts = (p.debug_flags & 1024) != 0;  // (timing aid: slots 5-7 stamp the issue phase instead)
   if (fine_ts) CB_TS(5);
-  // The prologue always requests NS-1 stages (keys past the split are clamped to valid ones and
-  // never used), unconditionally: the compiler then knows that the query loads above have at least
-  // that many requests behind them, and that the first stage's wait below covers them.  With a
-  // conditional prologue it waits for everything in flight before the first MFMA.
-  CB_ISSUE(0, 0);
-  if (fine_ts) CB_TS(6);
-  CB_ISSUE(1, 1);
-  if (fine_ts) CB_TS(7);
-  CB_ISSUE(2, 2);
-  const int nst_w = nst < NS - 1 ? NS - 1 : nst;  // stages requested
+  // The prologue requests PRO half-stages, and the rest of the ring goes out right behind the
+  // first stage's barrier -- all unconditionally (requests past the split's end repeat its last
+  // key and are never used), so every wave has a known number of requests behind its query loads,
+  // which is what the counted waits below rely on.  (A compute unit takes about 0.3 us to issue a
+  // half-stage's requests; with the whole ring in front of the first wait the first stage's
+  // arithmetic starts that much later for every half-stage added.)  A split of up to 32 NH keys
+  // -- the 7B-shaped workload's 288 -- is thereby requested in full before any of its arithmetic.
+#pragma unroll
+  for (int h = 0; h < PRO; h++) {
+    issue(h, h);
+    if (fine_ts && h == 1) CB_TS(6);
+    if (fine_ts && h == 3) CB_TS(7);
+  }
   CB_TS(2);
   if (tree_split) build_ancestor_sets(anc_sh, N, my_parent, jump_rounds(p.max_depth));  // uniform in the workgroup; hidden behind the first K/V wait
   // The first stage's wait, outside the ring loop: it also covers the query loads (older than the
   // whole prologue), whose registers are pinned here.
-  wait_vmcnt<8>();
+  wait_vmcnt<2 * (PRO - 2)>();
   ring_barrier();
 #pragma unroll
   for (int rr = 0; rr < R; rr++)
@@ -647,8 +663,8 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   CB_TS(3);
   // The logits item rides on the sweep's waits and barriers: its reduction here (its loads are
   // older still than the query's), the combination of the waves' candidates and the partial's
-  // store behind the first stage's barrier, the scan ticket at the last stage, whose vmcnt(0)
-  // covers that store.
+  // store behind the first stage's barrier, the scan ticket at the last stage if that stage's wait
+  // is a full one, which then covers that store.
   if constexpr (kHookEarly) hook->mid_consume();
 
 // the row tiles of a wave that lie past the sequence's rows are left out (R = 2: all, one or none)
@@ -660,43 +676,50 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     if (nvt == R) compute_stage<R, R>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);  \
     else if (R > 1) compute_stage<R, 1>(kp, vp, st, c2, key0, S, k1, need_mask, &anc_sh.anc[0][0], row_node, l);\
   } while (0)
-#define CB_STAGE_COMPUTE(J, s)                                                                     \
-  _Pragma("unroll") for (int h = SEQ ? 0 : gi; h < (SEQ ? G : gi + 1); h++) {                      \
-    const int key0 = k0 + (s) * SK + h * kStageKeys;                                               \
-    const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;                        \
-    if (key0 < k1 && nvt > 0)                                                                      \
-      CB_COMPUTE(K##J + h * kStageVecs, V##J + h * kStageVecs, key0, need_mask);                   \
+  // Stage s = half-stages 2s and 2s+1.  With SEQ = false wave group gi computes half-stage 2s + gi,
+  // with SEQ = true every wave computes both.  Each wave issues two requests per half-stage, and
+  // requests complete in order, so "at most 2 y requests outstanding" means that everything up to
+  // the y youngest half-stages has landed.  At the top of stage s the half-stages requested so far
+  // are the prologue's PRO, the rest of the ring (at the top of stage 0) and the refills made at
+  // the tops of stages 1 .. s-1.
+  int sa = 0;  // ring slot of half-stage 2s
+  for (int s = 0; s < nst; s++) {
+    const int requested = s == 0 ? PRO : (nhw < 2 * s + NH - 2 ? nhw : 2 * s + NH - 2);
+    const int younger = requested - (2 * s + 2);
+    static_assert(PRO - 2 <= 5 && NH - 4 <= 5, "the waits below cover up to five younger half-stages");
+    if (younger >= 5) wait_vmcnt<10>();
+    else if (younger == 4) wait_vmcnt<8>();
+    else if (younger == 3) wait_vmcnt<6>();
+    else if (younger == 2) wait_vmcnt<4>();
+    else if (younger == 1) wait_vmcnt<2>();
+    else wait_vmcnt<0>();
+    ring_barrier();  // every wave's share of stage s has landed, and nobody reads stage s-1 any more
+    const int sb = sa + 1 == NH ? 0 : sa + 1;
+    if (s == 0) {
+#pragma unroll
+      for (int h = PRO; h < NH; h++) issue(h, h);
+    } else {  // stage s-1's two slots take the next two half-stages
+      const int ha = 2 * s + NH - 2;
+      const int ra = sa >= 2 ? sa - 2 : sa - 2 + NH, rb = sa >= 1 ? sa - 1 : sa - 1 + NH;
+      if (ha < nh) issue(ha, ra);
+      if (ha + 1 < nh) issue(ha + 1, rb);
+    }
+    if constexpr (kHookEarly) {
+      if (s == 0) hook->mid_combine();
+      if (s == nst - 1 && younger <= 0) hook->early_ticket();  // behind this stage's vmcnt(0)
+    }
+#pragma unroll
+    for (int h = SEQ ? 0 : gi; h < (SEQ ? G : gi + 1); h++) {
+      const int key0 = k0 + (2 * s + h) * kStageKeys;
+      const bool need_mask = key0 + kStageKeys > S || key0 + kStageKeys > k1;
+      const uint4* const kp = ring + (h == 0 ? sa : sb) * (2 * kStageVecs);
+      if (key0 < k1 && nvt > 0) CB_COMPUTE(kp, kp + kStageVecs, key0, need_mask);
+    }
+    sa = sb + 1 == NH ? 0 : sb + 1;
   }
-#define CB_STAGE(J, JPREV)                                                                         \
-  {                                                                                                \
-    const int s = s0 + J;                                                                          \
-    if (s < nst) {                                                                                 \
-      { /* (stage 0 was waited for above: the compiler is to see the same wait in front of every */ \
-        /* stage's LDS reads, or it adds one of its own for everything in flight)               */ \
-        const int after = nst_w - 1 - s; /* stages requested after this one, at most NS-2 */      \
-        if (after >= 2) wait_vmcnt<8>(); else if (after == 1) wait_vmcnt<4>(); else wait_vmcnt<0>(); \
-        ring_barrier();                                                                            \
-      }                                                                                            \
-      if (s + NS - 1 < nst) CB_ISSUE(JPREV, s + NS - 1);                                           \
-      if constexpr (kHookEarly) {                                                                  \
-        if (J == 0 && s0 == 0) hook->mid_combine();                                                \
-        if (s == nst - 1 && nst >= NS - 1) hook->early_ticket(); /* behind this stage's vmcnt(0) */ \
-      }                                                                                            \
-      CB_STAGE_COMPUTE(J, s)                                                                       \
-    }                                                                                              \
-  }
-  for (int s0 = 0; s0 < nst; s0 += NS) {
-    CB_STAGE(0, 3)
-    CB_STAGE(1, 0)
-    CB_STAGE(2, 1)
-    CB_STAGE(3, 2)
-  }
-#undef CB_STAGE_COMPUTE
-#undef CB_STAGE
 #undef CB_COMPUTE
-#undef CB_ISSUE
 
-  if (nst < NS - 1) wait_vmcnt<0>();  // (a short split: the unused rest of the prologue must land before the ring is reused)
+  wait_vmcnt<0>();  // (a short split: the unused rest of the prologue must land before the ring is reused)
   CB_TS(4);
   if (p.debug_flags & 8) return;  // (timing aid: stop after the key sweep)
   if constexpr (kHookEarly) {
@@ -713,26 +736,25 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   if constexpr (kTwoGroups) {
     __syncthreads();  // every wave is done with the ring
     const int lane = wi * 64 + l;
-    float2* const park_ml = reinterpret_cast<float2*>(V0);
+    uint4* const park = ring;  // 16 accumulator tiles x 256 lanes x 16 B, then the (mref, l) pairs
+    float2* const park_ml = reinterpret_cast<float2*>(ring + 16 * 256);
     // (the group index is a compile-time constant inside, so that ring slots and accumulators keep
     // constant indices)
     auto park_half = [&](auto gic) {
       constexpr int GI = decltype(gic)::value;
-      uint4* const park[4] = {K0, K1, K2, K3};  // 16 accumulator tiles x 256 lanes x 16 B
 #pragma unroll
       for (int rr = 0; rr < R; rr++) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
           const int dt = 4 * (1 - GI) + i;  // the partner's half
           const int slot = rr * 8 + dt;
-          park[slot >> 2][(slot & 3) * 256 + lane] = __builtin_bit_cast(uint4, st.o[rr][dt]);
+          park[slot * 256 + lane] = __builtin_bit_cast(uint4, st.o[rr][dt]);
         }
         park_ml[(GI * R + rr) * 256 + lane] = float2{st.mref[rr], st.lacc[rr][0]};
       }
     };
     auto take_half = [&](auto gic) {
       constexpr int GI = decltype(gic)::value;
-      uint4* const park[4] = {K0, K1, K2, K3};
 #pragma unroll
       for (int rr = 0; rr < R; rr++) {
         const float2 ml2 = park_ml[((1 - GI) * R + rr) * 256 + lane];
@@ -743,7 +765,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
         for (int i = 0; i < 4; i++) {
           const int dt = 4 * GI + i;
           const int slot = rr * 8 + dt;
-          const floatx4 a = __builtin_bit_cast(floatx4, park[slot >> 2][(slot & 3) * 256 + lane]);
+          const floatx4 a = __builtin_bit_cast(floatx4, park[slot * 256 + lane]);
           st.o[rr][dt] = st.o[rr][dt] * w0 + a * w1;
         }
         st.lacc[rr][0] = st.lacc[rr][0] * w0 + ml2.y * w1;
@@ -797,8 +819,8 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
           else __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + dt * 512 + l * 8, 0, kAgentCoherent);
         }
         if (kg == 0 && (!kTwoGroups || gi == 0)) {
-          // the merge works in the natural-log domain: m = ln of the reference weight 2^(c2*mref)
-          const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2 * 0.6931471805599453f;
+          // m = log2 of the reference weight 2^(c2*mref)
+          const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2;  // log2 units
           const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
           if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + kUnitMl + c * 8, 0, 0);
           else __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + kUnitMl + c * 8, 0, kAgentCoherent);
@@ -822,7 +844,6 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   CB_TS(5);
-  const int tiles = p.grid_y / p.Hkv;
   // (cooperative merge: the tiles' words are polled, so each tile has a 4 KiB stretch of its own
   // in a separate area -- neighbours in one line would all be served by one memory channel)
   const int64_t tile_id = ((int64_t)b * p.Hkv + hk) * tiles + rt;
@@ -893,7 +914,6 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     hook->accept_first();
     hook->stamp(5);
   }
-  bool reset_late = false;
   if (tid == 64) {
     unsigned long long tot = __hip_atomic_fetch_add(ticket, arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + arrive;
     const bool completes = (tot & kArrivals) == (unsigned long long)nsplit_b;
@@ -922,43 +942,72 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     if (completes) {
       todo2 = __hip_atomic_load(gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~todo;
       if (todo2 != 0) __hip_atomic_store(gave_up, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (!(p.debug_flags & 2048)) __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
-      else reset_late = true;
+      __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
     } else if (own_bit && todo != 0) {
       __hip_atomic_fetch_and(gave_up, ~(1ull << split), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     merge_todo2 = todo2;
     __hip_atomic_store(&merge_flag2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
+  // Unit u of the tile = (16-row tile u / 8, dim tile u % 8); this workgroup's own slice holds the
+  // units split, split + nsplit_b, ...; its k-th unit goes to wave (k + 1) % NW.  What a wave needs
+  // for its first unit -- the lane's output row, the partials' offsets -- is worked out before it
+  // waits, so that the loads go out as soon as the verdict is in.
+  constexpr int NW = NT / 64;
+  constexpr int NU = (RT / 16) * 8;
+  const int nslots = nsplit_b;
+  auto unit_row = [&](int u, int64_t* gr, uint32_t* ub) {  // false: no rows in this unit's tile
+    const int tl = u >> 3;
+    const int row = row0 + tl * 16 + c;
+    if (row - c >= M) return false;
+    const int node = row / g, hg = row - node * g;
+    *gr = row < M ? (int64_t)(off + node) * p.Hq + hk * g + hg : -1;
+    *ub = (uint32_t)(hk * ((M + 15) >> 4) + (row0 >> 4) + tl) * (uint32_t)p.nsplit * (uint32_t)kUnitBytes;
+    return true;
+  };
+  auto merge_one = [&](int u, int64_t gr, uint32_t ub, int flag) {
+    int64_t gr1[1] = {gr};
+    uint32_t ub1[1] = {ub};
+    const int dt = u & 7;
+    if (nslots <= 8) {  // (one batch in the common cases)
+      if (flag == 1) merge_tile<1, 1, 0, 8>(prsrc, gr1, ub1, gout, nslots, dt, l);
+      else merge_tile<1, 1, kAgentCoherent, 8>(prsrc, gr1, ub1, gout, nslots, dt, l);
+    } else {
+      if (flag == 1) merge_tile<1, 1, 0, 16>(prsrc, gr1, ub1, gout, nslots, dt, l);
+      else merge_tile<1, 1, kAgentCoherent, 16>(prsrc, gr1, ub1, gout, nslots, dt, l);
+    }
+  };
+  const int u_first = split + ((w + NW - 1) % NW) * nsplit_b;  // this wave's first unit of the own slice
+  int64_t gr_first = -1;
+  uint32_t ub_first = 0;
+  const bool have_first = u_first < NU && unit_row(u_first, &gr_first, &ub_first);
   // the waves wait for thread 64's verdicts in LDS (no barrier: wave 0 may still be busy)
   int flag;
   while ((flag = __hip_atomic_load(&merge_flag, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP)) == 0) __builtin_amdgcn_s_sleep(1);
-  int k = 0;  // running number of this workgroup's units: unit k goes to wave (k + 1) % NW
-  auto merge_slices = [&](unsigned long long todo) {
-    constexpr int NW = NT / 64;
-    constexpr int NU = (RT / 16) * 8;  // units of the workgroup's tile
+  if (do_ts64) ts[8] = wall_clock64();
+  auto merge_slices = [&](unsigned long long todo, bool first_done) {
+    int k = 0;  // running number of the units of the slices in `todo`
     for (int s2 = 0; s2 < nsplit_b; s2++) {
       if (!((todo >> s2) & 1ull)) continue;
       for (int u = s2; u < NU; u += nsplit_b, k++) {
-        if ((k + 1) % NW != w) continue;
-        const int tl = u >> 3, dt = u & 7;
-        const int row = row0 + tl * 16 + c;
-        if (row - c >= M) continue;
-        const int node = row / g, hg = row - node * g;
-        int64_t gr1[1] = {row < M ? (int64_t)(off + node) * p.Hq + hk * g + hg : -1};
-        uint32_t ub1[1] = {(uint32_t)(hk * ((M + 15) >> 4) + (row0 >> 4) + tl) * (uint32_t)p.nsplit * (uint32_t)kUnitBytes};
-        if (flag == 1) merge_tile<1, 1, 0, 8>(prsrc, gr1, ub1, gout, nsplit_b, dt, l);
-        else merge_tile<1, 1, kAgentCoherent, 8>(prsrc, gr1, ub1, gout, nsplit_b, dt, l);
+        if ((k + 1) % NW != w || (first_done && u == u_first)) continue;
+        int64_t gr;
+        uint32_t ub;
+        if (unit_row(u, &gr, &ub)) merge_one(u, gr, ub, flag);
       }
     }
   };
-  merge_slices(merge_todo);
-  while (__hip_atomic_load(&merge_flag2, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) __builtin_amdgcn_s_sleep(1);
-  if (merge_todo2 != 0) merge_slices(merge_todo2);
-  if (reset_late) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __hip_atomic_store(ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long todo1 = merge_todo;
+  if (todo1 == (1ull << split)) {  // the usual case: the own slice
+    if (have_first) merge_one(u_first, gr_first, ub_first, flag);
+    if (u_first + NW * nsplit_b < NU) merge_slices(todo1, true);
+  } else if (todo1 != 0) {
+    merge_slices(todo1, false);
   }
+  if (do_ts64) ts[9] = wall_clock64();
+
+  while (__hip_atomic_load(&merge_flag2, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) __builtin_amdgcn_s_sleep(1);
+  if (merge_todo2 != 0) merge_slices(merge_todo2, false);
   if (do_ts64) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     ts[7] = wall_clock64();
@@ -985,7 +1034,7 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p, SeqMeta met
   const SeqMetaLanes ml = seq_meta_prefetch(meta);
   __shared__ unsigned long long ts_sh[16];
   attn_tile<R, G, SEQ, false>(p, ml, ts0, nullptr, ts_sh);
-  flush_timestamps(p, ts_sh, false);
+  flush_timestamps(p, ts_sh, true);
 }
 
 // The whole verification in one launch: every workgroup does its attention duty (a tile's split,
@@ -1032,7 +1081,7 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
   floatx4 acc[NDT];
 #pragma unroll
   for (int i = 0; i < NDT; i++) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float lsum = 0.f, m_run = -INFINITY;
+  float lsum = 0.f, m_run = -3.0e38f;  // (kept finite: a slot without a visible key carries m = -inf and gets weight 0)
   constexpr int BS = 8;
   for (int t0 = 0; t0 < ns; t0 += BS) {
     uint2 v[BS][NDT];
@@ -1045,19 +1094,19 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
 #pragma unroll
       for (int i = 0; i < NDT; i++) v[u][i] = *reinterpret_cast<const uint2*>(tb + (dt0 + i) * 512 + l * 8);
     }
-    float mb = -INFINITY;
+    __builtin_amdgcn_sched_barrier(0);  // (every load of the batch requested before the first result is looked at)
+    float m_new = m_run;
 #pragma unroll
-    for (int u = 0; u < BS; u++)
-      if (t0 + u < ns) mb = fmaxf(mb, ml[u].x);
-    const float m_new = fmaxf(m_run, mb);
-    const float resc = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+    for (int u = 0; u < BS; u++) m_new = fmaxf(m_new, ml[u].x);
+    const float resc = __builtin_amdgcn_exp2f(m_run - m_new);
 #pragma unroll
     for (int i = 0; i < NDT; i++) acc[i] *= resc;
     lsum *= resc;
     m_run = m_new;
 #pragma unroll
     for (int u = 0; u < BS; u++) {
-      const float wgt = (t0 + u < ns && ml[u].x != -INFINITY) ? __expf(ml[u].x - m_new) : 0.f;
+      float wgt = __builtin_amdgcn_exp2f(ml[u].x - m_new);  // m is stored in log2 units
+      wgt = (t0 + u < ns) ? wgt : 0.f;
       lsum = fmaf(ml[u].y, wgt, lsum);
 #pragma unroll
       for (int i = 0; i < NDT; i++) {
@@ -1068,7 +1117,7 @@ __global__ __launch_bounds__(256) void k_merge_partials_bf16(AttnParams p, SeqMe
       }
     }
   }
-  const float inv = 1.0f / lsum;
+  const float inv = __builtin_amdgcn_rcpf(lsum);
   const int node = row / g, hg = row - node * g;
   uint16_t* orow = reinterpret_cast<uint16_t*>(p.out) + ((int64_t)(off + node) * p.Hq + hk * g + hg) * D;
 #pragma unroll
