@@ -7,9 +7,9 @@
  * that verification for one attention layer plus the final logits:
  *
  *   cb_verify_tree   tree attention -- every tree node attends to the KV-cached prefix and to its
- *                    own ancestors in the draft tree (Section 3.2, "a token attends only to its
- *                    ancestor tokens"; a node also sees itself, which makes every root-to-leaf
- *                    path ordinary causal attention) -- followed by the greedy acceptance of
+ *                    own ancestors in the draft tree (the tree attention of Section 3.2; a node
+ *                    also sees itself, which makes every root-to-leaf path ordinary causal
+ *                    attention) -- followed by the greedy acceptance of
  *                    Section 3.2: the token the model generates at a node is the first maximum of
  *                    the node's logits row; the longest branch prefix whose draft tokens equal what
  *                    was generated at their parents is accepted, and the pass always yields one

@@ -24,6 +24,7 @@ struct WsLayout {
   int amax_chunks;
   int max_total_nodes;
   int max_splits;
+  int scalar_splits;  // split count the scalar kernel's fp32 partials have room for
   int ticket_count;
 };
 
@@ -78,11 +79,24 @@ WsLayout ws_layout(const cb_config& c) {
   // argmax partials of the one-launch verification, one 128-byte line each (it takes sequences of at most 64 nodes)
   L.amax_lines = take((size_t)c.max_batch * std::min(c.max_nodes, 64) * L.amax_chunks * 128);
   L.dbg = take(1024 * 8 * 8);
-  L.partial = take(std::max(mt * c.num_q_heads * (size_t)L.max_splits * partial_stride(c.head_dim) * 4,
-                            attn_mfma_partial_bytes(mt, c.num_q_heads, c.num_kv_heads, c.max_batch, L.max_splits)));
+  // The scalar kernel's fp32 partials are 8 times the size of the MFMA kernel's.  A configuration
+  // the MFMA kernel takes (bf16, head_dim 128) runs the scalar one only on request (option
+  // "attn_impl" = 1, a test aid): it gets room for 8 splits there, not for max_splits.
+  const bool mfma_cfg = c.qkv_dtype == CB_BF16 && c.head_dim == 128;
+  L.scalar_splits = mfma_cfg ? std::min(L.max_splits, 8) : L.max_splits;
+  const size_t scalar_bytes = mt * c.num_q_heads * (size_t)L.scalar_splits * partial_stride(c.head_dim) * 4;
+  const size_t mfma_bytes = mfma_cfg ? attn_mfma_partial_bytes(mt, c.num_q_heads, c.num_kv_heads, c.max_batch, L.max_splits) : 0;
+  L.partial = take(std::max(scalar_bytes, mfma_bytes));
   L.total = o;
   return L;
 }
+
+struct Plan {
+  int impl;    // 1 scalar, 2 MFMA
+  int nsplit;  // partial slots per row
+  int chunk;   // keys per split
+  int max_nodes, max_len;
+};
 
 }  // namespace
 
@@ -114,6 +128,7 @@ struct cb_ctx {
   hipEvent_t ev0, ev1, ev_fork, ev_join;
   hipStream_t aux;  // second stream (default priority) for the logits scan beside the attention
   bool ev_valid;
+  bool counters_dirty = false;  // a launch failed: the tickets may be left non-zero
   char err[256];
 
   template <typename T>
@@ -135,6 +150,15 @@ int set_err(cb_ctx* ctx, int code, const char* fmt, ...) {
   do {                                                                                            \
     hipError_t e__ = (call);                                                                      \
     if (e__ != hipSuccess) return set_err(ctx, CB_EHIP, "%s: %s", #call, hipGetErrorString(e__)); \
+  } while (0)
+// the same for the launches of run_pipeline: a failure there may leave tickets behind
+#define CB_LAUNCH(ctx, call)                                                                      \
+  do {                                                                                            \
+    hipError_t e__ = (call);                                                                      \
+    if (e__ != hipSuccess) {                                                                      \
+      (ctx)->counters_dirty = true;                                                               \
+      return set_err(ctx, CB_EHIP, "%s: %s", #call, hipGetErrorString(e__));                     \
+    }                                                                                             \
   } while (0)
 
 bool make_kv_addr(const cb_config& c, const cb_kv_layer& l, KvAddr* a) {
@@ -159,15 +183,8 @@ bool make_kv_addr(const cb_config& c, const cb_kv_layer& l, KvAddr* a) {
   return true;
 }
 
-struct Plan {
-  int impl;    // 1 scalar, 2 MFMA
-  int nsplit;  // partial slots per row
-  int chunk;   // keys per split
-  int max_nodes, max_len;
-};
-
 // Pure host arithmetic: no device call, no context state beyond the three numbers passed in.
-Plan plan_attention(const cb_config& c, int max_splits, int opt_impl, int opt_splits, int batch,
+Plan plan_attention(const cb_config& c, int max_splits, int scalar_splits, int opt_impl, int opt_splits, int batch,
                     const int32_t* kv_len, const int32_t* node_offsets) {
   Plan p{};
   int64_t rows = 0;
@@ -179,6 +196,7 @@ Plan plan_attention(const cb_config& c, int max_splits, int opt_impl, int opt_sp
   }
   const bool mfma_ok = c.qkv_dtype == CB_BF16 && c.head_dim == 128;
   p.impl = (opt_impl == 1 || !mfma_ok) ? 1 : 2;
+  if (p.impl == 1) max_splits = scalar_splits;
   int nsplit;
   if (opt_splits > 0) {
     nsplit = (int)std::min<int64_t>(opt_splits, max_splits);
@@ -263,7 +281,14 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   for (int b = 0; b < batch; b++) meta.kv_len[b] = kv_len[b];
   for (int b = 0; b <= batch; b++) meta.node_off[b] = node_offsets[b];
   const int total = node_offsets[batch];
-  const Plan plan = plan_attention(c, ctx->lay.max_splits, ctx->opt_impl, ctx->opt_splits, batch, kv_len, node_offsets);
+  if (ctx->counters_dirty) {  // (after a failed launch: the kernels rely on tickets that are zero between launches)
+    const hipError_t e1 = launch_zero_words(st, ctx->dev<unsigned long long>(ctx->lay.tickets), ctx->lay.ticket_count / 2, 1, 1);
+    const hipError_t e2 = launch_zero_words(st, ctx->dev<unsigned long long>(ctx->lay.coop_tickets), kCoopTiles, kCoopTicketStride / 8, 2);
+    const hipError_t e3 = launch_zero_words(st, ctx->dev<unsigned long long>(ctx->lay.amax_tickets), CB_MAX_BATCH / 2, 1, 1);
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) return set_err(ctx, CB_EHIP, "clearing the tickets after a failed launch failed");
+    ctx->counters_dirty = false;
+  }
+  const Plan plan = plan_attention(c, ctx->lay.max_splits, ctx->lay.scalar_splits, ctx->opt_impl, ctx->opt_splits, batch, kv_len, node_offsets);
 
   AttnParams ap{};
   ap.q = q;
@@ -326,12 +351,12 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   if (fused) {
   } else if (stages & 4) {
     const bool carry = !use_mfma && (stages & 1);
-    CB_HIP(ctx, launch_argmax(scan_stream, logits, c.logits_dtype, total, c.vocab_size,
+    CB_LAUNCH(ctx, launch_argmax(scan_stream, logits, c.logits_dtype, total, c.vocab_size,
                               ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
                               carry ? d_parent : nullptr, c.max_depth, carry ? ctx->dev<uint32_t>(ctx->lay.anc) : nullptr,
                               carry ? ctx->dev<int32_t>(ctx->lay.status) : nullptr));
   } else if (!use_mfma && (stages & 1)) {
-    CB_HIP(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
+    CB_LAUNCH(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
                                     ctx->dev<int32_t>(ctx->lay.status)));
   }
   if (fork) CB_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux));
@@ -349,17 +374,17 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
     lw.accept.partial = ctx->dev<ArgmaxPartial>(ctx->lay.amax_lines);
     lw.accept.slot_stride = 16;
     lw.partial_out = ctx->dev<ArgmaxPartial>(ctx->lay.amax_lines);
-    CB_HIP(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total, fused ? &lw : nullptr));  // merges its own splits
+    CB_LAUNCH(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total, fused ? &lw : nullptr));  // merges its own splits
   } else {
-    CB_HIP(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
-    if (plan.nsplit > 1) CB_HIP(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
+    CB_LAUNCH(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
+    if (plan.nsplit > 1) CB_LAUNCH(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
   }
   if (timing) {
     CB_HIP(ctx, hipEventRecord(ctx->ev1, st));
     ctx->ev_valid = true;
   }
   if (fork) CB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
-  if ((stages & 8) && !fused) CB_HIP(ctx, launch_accept(st, batch, meta, acc));
+  if ((stages & 8) && !fused) CB_LAUNCH(ctx, launch_accept(st, batch, meta, acc));
   if (!(stage_mask & 8)) return CB_OK;  // attention alone leaves the state of the last verification as it is
   ctx->launch_info[0] = use_mfma ? 2 : 1;
   ctx->launch_info[1] = plan.nsplit;
@@ -410,7 +435,8 @@ int cb_plan_attention(const cb_config* cfg, int32_t batch, const int32_t* kv_len
     const int64_t n = (int64_t)node_offsets[b + 1] - node_offsets[b];
     if (n < 1 || n > cfg->max_nodes || kv_len[b] < 0 || (int64_t)kv_len[b] + n > (1ll << 30)) return CB_EINVAL;
   }
-  const Plan p = plan_attention(*cfg, effective_max_splits(*cfg), 0, forced_splits, batch, kv_len, node_offsets);
+  const WsLayout lay = ws_layout(*cfg);
+  const Plan p = plan_attention(*cfg, lay.max_splits, lay.scalar_splits, 0, forced_splits, batch, kv_len, node_offsets);
   const int g = cfg->num_q_heads / cfg->num_kv_heads;
   const int tile = p.impl == 2 ? attn_mfma_tile_rows(p.max_nodes * g) : 1;
   int64_t wgs = 0;

@@ -66,10 +66,10 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnParams p, SeqMeta meta) {
   const int off = meta.node_off[b];
   const int N = meta.node_off[b + 1] - off;
   const int S = meta.kv_len[b];
-  const int i = blockIdx.y / p.Hq, h = blockIdx.y - i * p.Hq;
+  const int i = blockIdx.x / p.Hq, h = blockIdx.x - i * p.Hq;  // (rows on x: up to 256 nodes x 1024 heads)
   if (i >= N) return;
   const int len = S + N;
-  const int k0 = blockIdx.x * p.chunk;
+  const int k0 = blockIdx.y * p.chunk;
   if (k0 >= len) return;
   const int k1 = (k0 + p.chunk < len) ? k0 + p.chunk : len;
   const int nsplit_b = (len + p.chunk - 1) / p.chunk;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnParams p, SeqMeta meta) {
     if (nsplit_b == 1) {
       st_elem(reinterpret_cast<T*>(p.out) + row * D + tid, o / l_run);
     } else {
-      float* pr = p.partial + (row * p.nsplit + blockIdx.x) * partial_stride(D);
+      float* pr = p.partial + (row * p.nsplit + blockIdx.y) * partial_stride(D);
       pr[tid] = o;
       if (tid == 0) { pr[D] = m_run; pr[D + 1] = l_run; }
     }
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void k_attn_simt(AttnParams p, SeqMeta meta) {
 
 hipError_t launch_attn_simt(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int dtype,
                             int max_nodes_in_call) {
-  dim3 grid(p.nsplit, max_nodes_in_call * p.Hq, p.batch);
+  dim3 grid(max_nodes_in_call * p.Hq, p.nsplit, p.batch);
   dim3 block(256);
   if (dtype == CB_F32 && p.D == 64) hipLaunchKernelGGL((k_attn_simt<float, 64>), grid, block, 0, st, p, meta);
   else if (dtype == CB_F32 && p.D == 128) hipLaunchKernelGGL((k_attn_simt<float, 128>), grid, block, 0, st, p, meta);

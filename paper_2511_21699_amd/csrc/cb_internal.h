@@ -181,6 +181,8 @@ struct ArgmaxPartial {
 // ---- launchers (defined in the .hip files); all enqueue on `st` and return the launch status
 hipError_t launch_tree_prepare(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
                                int max_depth, uint32_t* anc, int32_t* status);
+// zeroes `run` 64-bit words at each of `count` places `stride` words apart
+hipError_t launch_zero_words(hipStream_t st, unsigned long long* base, int count, int stride, int run);
 // scans the logits; with prep_parent != nullptr the same launch also builds the ancestor sets
 hipError_t launch_argmax(hipStream_t st, const void* logits, int dtype, int rows, int64_t V,
                          ArgmaxPartial* partial, int nchunks, int batch, const SeqMeta& meta,

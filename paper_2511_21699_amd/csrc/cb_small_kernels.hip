@@ -57,6 +57,19 @@ __global__ __launch_bounds__(256) void k_tree_prepare(SeqMeta meta, const int32_
   tree_prepare_block(sh, meta, blockIdx.x, parent, max_depth, anc, status);
 }
 
+// Zero-fill of `count` 64-bit words, `stride` words apart, `run` words at each place (counters that
+// must start at zero; a kernel rather than a memset so that the call can be captured into a graph).
+__global__ __launch_bounds__(256) void k_zero_words(unsigned long long* base, int count, int stride, int run) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < count * run) base[(int64_t)(i / run) * stride + i % run] = 0ull;
+}
+
+hipError_t launch_zero_words(hipStream_t st, unsigned long long* base, int count, int stride, int run) {
+  if (count <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_zero_words, dim3((count * run + 255) / 256), dim3(256), 0, st, base, count, stride, run);
+  return hipGetLastError();
+}
+
 hipError_t launch_tree_prepare(hipStream_t st, int batch, const SeqMeta& meta, const int32_t* parent,
                                int max_depth, uint32_t* anc, int32_t* status) {
   hipLaunchKernelGGL(k_tree_prepare, dim3(batch), dim3(256), 0, st, meta, parent, max_depth, anc, status);

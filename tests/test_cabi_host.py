@@ -33,7 +33,11 @@ def _kv(cap=100, paged=False):
 
 def test_workspace_bytes_and_bad_configs():
     good = B.make_config(32, 8, 128, "bf16", "bf16", 1, 128, 8, 32000)
-    assert B.workspace_bytes(good) > 128 * 32 * 64 * 130 * 4
+    # bf16 / head_dim 128: room for the MFMA kernel's bf16 partials at 64 splits (4,224 bytes per 16-row tile and
+    # split), not for the scalar kernel's fp32 ones at that split count
+    assert 128 * 32 // 16 * 64 * 4224 < B.workspace_bytes(good) < 128 * 32 * 64 * 132 * 4
+    scalar = B.make_config(32, 8, 128, "f32", "f32", 1, 128, 8, 32000)
+    assert B.workspace_bytes(scalar) > 128 * 32 * 64 * 132 * 4
     for bad in (B.make_config(32, 5, 128, "bf16", "bf16", 1, 64, 6, 100),
                 B.make_config(32, 8, 96, "bf16", "bf16", 1, 64, 6, 100),
                 B.make_config(32, 8, 128, "bf16", "bf16", 1, 257, 6, 100),
@@ -148,3 +152,4 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "one GPU" in r.stderr
     assert r.stdout.strip() == ""
+
