@@ -171,6 +171,24 @@ int cb_tree_attention_device(cb_ctx *ctx, void *hip_stream, int32_t batch, const
                              void *attn_out);
 
 /*
+ * cb_tree_attention_device for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  No context and no workspace: the configuration is
+ * passed with every call, and the scratch memory the kernels need (split partials, merge tickets,
+ * ancestor sets) is a fixed 32 MiB array inside the library's device image, which every GPU the
+ * library runs on holds until the process ends.  The call allocates nothing on the host or the device
+ * and only enqueues kernels on `hip_stream`.  A call whose shapes need more scratch than the array
+ * holds returns CB_ECAP (text via cb_last_error(NULL)); of the five benchmark workloads the batched
+ * ragged one is beyond it.  All calls on one GPU share the array, which keeps the last call's
+ * contents (the counters that must start at zero are cleared by the call itself): calls that overlap
+ * on one GPU -- from different streams or threads -- race and give undefined results.  Results are
+ * those of cb_tree_attention_device for the same arguments.
+ */
+int cb_tree_attention_noalloc(const cb_config *cfg, void *hip_stream, int32_t batch, const void *q,
+                              const cb_kv_layer *kv, const int32_t *kv_len,
+                              const int32_t *node_offsets, const int32_t *d_tree_parent,
+                              void *attn_out);
+
+/*
  * Moves the K/V of the path accepted by the last verify call of this context into place, for
  * `num_layers` caches that share one geometry (capacity, block table, layout) and differ only in
  * their k/v pointers: for j = 1..L_b, slot S_b+j <- slot S_b+path_b[j].  Enqueues on `hip_stream`.

@@ -20,7 +20,7 @@ CB_OK, CB_EINVAL, CB_ETREE, CB_ECAP, CB_ESTATE, CB_EHIP = range(6)
 CB_LAYOUT_TOKEN_MAJOR, CB_LAYOUT_HEAD_MAJOR = 0, 1
 ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_ESTATE", 5: "CB_EHIP"}
 
-EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device", "cb_tree_attention_device",
+EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device", "cb_tree_attention_device", "cb_tree_attention_noalloc",
            "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
            "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_probe_load_order", "cb_probe_stream_read", "cb_last_error",
            "cb_destroy"]
@@ -68,6 +68,7 @@ def load():
     L.cb_verify_tree.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, i32p, i32p, vp, vp, i32p, i32p]
     L.cb_verify_tree_device.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, vp, vp, vp, vp, vp, vp]
     L.cb_tree_attention_device.argtypes = [vp, vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, vp, vp]
+    L.cb_tree_attention_noalloc.argtypes = [C.POINTER(CbConfig), vp, C.c_int32, vp, C.POINTER(CbKvLayer), i32p, i32p, vp, vp]
     L.cb_compact_kv.argtypes = [vp, vp, C.c_int32, C.POINTER(CbKvLayer), i32p]
     L.cb_get_path.argtypes = [vp, i32p]
     L.cb_get_argmax.argtypes = [vp, i32p]
@@ -164,6 +165,18 @@ def probe_stream_read(d_src, nbytes: int, d_sink, stream=None) -> None:
                                      C.c_void_p(d_sink.data_ptr()))
     if rc:
         raise CbError(rc, "cb_probe_stream_read rejected the arguments")
+
+
+def tree_attention_noalloc(cfg: CbConfig, q, kv: CbKvLayer, kv_len, node_offsets, d_parent, attn_out, stream=None) -> None:
+    """cb_tree_attention_noalloc on torch tensors: no context, no workspace, launches only."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    kv_len, node_offsets = _i32(kv_len), _i32(node_offsets)
+    L = load()
+    rc = L.cb_tree_attention_noalloc(C.byref(cfg), C.c_void_p(st.cuda_stream), kv_len.shape[0], q.data_ptr(), C.byref(kv),
+                                     _ip(kv_len), _ip(node_offsets), d_parent.data_ptr(), attn_out.data_ptr())
+    if rc:
+        raise CbError(rc, L.cb_last_error(None).decode())
 
 
 def workspace_bytes(cfg: CbConfig) -> int:

@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "cb_logits.h"
@@ -14,6 +15,15 @@ using namespace cb;
 namespace {
 
 thread_local char g_init_err[256] = "";
+
+// Scratch memory of cb_tree_attention_noalloc: a fixed array in the library's own device image
+// (every GPU the library runs on holds one copy until the process ends).  In host code the array's
+// name is only a handle: its address on a device comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = 32u << 20;
+__device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_static_scratch_ptr[kMaxDevices];  // per device, filled on first use (under g_static_mutex)
+std::mutex g_static_mutex;
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -128,6 +138,7 @@ struct cb_ctx {
   hipEvent_t ev0, ev1, ev_fork, ev_join;
   hipStream_t aux;  // second stream (default priority) for the logits scan beside the attention
   bool ev_valid;
+  const Plan* fixed_plan = nullptr;  // (cb_tree_attention_noalloc: the plan its scratch layout was cut for)
   bool counters_dirty = false;  // a launch failed: the tickets may be left non-zero
   char err[256];
 
@@ -288,7 +299,8 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
     if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) return set_err(ctx, CB_EHIP, "clearing the tickets after a failed launch failed");
     ctx->counters_dirty = false;
   }
-  const Plan plan = plan_attention(c, ctx->lay.max_splits, ctx->lay.scalar_splits, ctx->opt_impl, ctx->opt_splits, batch, kv_len, node_offsets);
+  const Plan plan = ctx->fixed_plan ? *ctx->fixed_plan
+                                    : plan_attention(c, ctx->lay.max_splits, ctx->lay.scalar_splits, ctx->opt_impl, ctx->opt_splits, batch, kv_len, node_offsets);
 
   AttnParams ap{};
   ap.q = q;
@@ -586,6 +598,80 @@ int cb_tree_attention_device(cb_ctx* ctx, void* hip_stream, int32_t batch, const
   if (rc) return rc;
   return run_pipeline(ctx, static_cast<hipStream_t>(hip_stream), batch, q, kv, kv_len, node_offsets, d_tree_parent,
                       nullptr, nullptr, attn_out, nullptr, nullptr, 3);
+}
+
+int cb_tree_attention_noalloc(const cb_config* cfg, void* hip_stream, int32_t batch, const void* q, const cb_kv_layer* kv,
+                              const int32_t* kv_len, const int32_t* node_offsets, const int32_t* d_tree_parent,
+                              void* attn_out) {
+  g_init_err[0] = 0;
+  if (!config_ok(cfg, g_init_err, sizeof g_init_err)) return CB_EINVAL;
+  if (!q || !kv || !kv_len || !node_offsets || !d_tree_parent || !attn_out) return set_err(nullptr, CB_EINVAL, "null argument");
+  if (batch < 1 || batch > cfg->max_batch) return set_err(nullptr, CB_EINVAL, "batch %d outside [1, %d]", batch, cfg->max_batch);
+  if (((uintptr_t)q | (uintptr_t)kv->k | (uintptr_t)kv->v | (uintptr_t)attn_out) & 15)
+    return set_err(nullptr, CB_EINVAL, "device pointers must be 16-byte aligned");
+  // A context on the stack, never handed out: configuration, options at their defaults, and a
+  // workspace layout cut from the static array for exactly this call's shapes.
+  cb_ctx tmp{};
+  tmp.cfg = *cfg;
+  tmp.opt_stages = 15;
+  tmp.opt_coop = 1;
+  tmp.opt_spin = 256;
+  int rc = check_device_shapes(&tmp, batch, kv, kv_len, node_offsets);
+  if (rc) {
+    memcpy(g_init_err, tmp.err, sizeof g_init_err);
+    return rc;
+  }
+  const int total = node_offsets[batch];
+  const WsLayout full = ws_layout(*cfg);
+  const Plan plan = plan_attention(*cfg, full.max_splits, full.scalar_splits, 0, 0, batch, kv_len, node_offsets);
+  const int g = cfg->num_q_heads / cfg->num_kv_heads;
+  const int tile_count = batch * cfg->num_kv_heads * ((plan.max_nodes * g + kRowTile - 1) / kRowTile);
+  WsLayout L{};
+  L.max_total_nodes = total;
+  L.max_splits = plan.nsplit;
+  L.scalar_splits = plan.nsplit;
+  L.amax_chunks = full.amax_chunks;
+  L.ticket_count = 4 * tile_count;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  L.status = take(4);
+  L.tickets = take((size_t)L.ticket_count * 4);
+  L.coop_tickets = take((size_t)kCoopTiles * kCoopTicketStride);
+  L.anc = take((size_t)total * kAncWords * 4);
+  L.dbg = L.anc;                    // (never written: the timing aid is off)
+  L.partial = take(plan.nsplit <= 1 ? 0
+                   : plan.impl == 2 ? attn_mfma_partial_bytes(total, cfg->num_q_heads, cfg->num_kv_heads, batch, plan.nsplit)
+                                    : (size_t)total * cfg->num_q_heads * plan.nsplit * partial_stride(cfg->head_dim) * 4);
+  L.total = o;
+  if (L.total > kStaticScratchBytes)
+    return set_err(nullptr, CB_ECAP, "this call needs %zu bytes of scratch memory, the library's fixed buffer has %zu", L.total, kStaticScratchBytes);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) return set_err(nullptr, CB_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_scratch_ptr[dev]) {
+      void* ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch));
+      if (e != hipSuccess || !ptr) return set_err(nullptr, CB_EHIP, "hipGetSymbolAddress: %s", hipGetErrorString(e));
+      g_static_scratch_ptr[dev] = ptr;
+    }
+    base = g_static_scratch_ptr[dev];
+  }
+  tmp.lay = L;
+  tmp.fixed_plan = &plan;
+  tmp.ws = static_cast<char*>(base);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // The array is shared by every call on this GPU and keeps the last call's contents: the words that
+  // must start at zero are cleared here, by a kernel (a caller may be capturing the stream).
+  e = launch_zero_words(st, tmp.dev<unsigned long long>(L.status), 1, 1, 1);
+  if (e == hipSuccess) e = launch_zero_words(st, tmp.dev<unsigned long long>(L.tickets), L.ticket_count / 2, 1, 1);
+  if (e == hipSuccess) e = launch_zero_words(st, tmp.dev<unsigned long long>(L.coop_tickets), std::min(tile_count, kCoopTiles), kCoopTicketStride / 8, 2);
+  if (e != hipSuccess) return set_err(nullptr, CB_EHIP, "clearing the scratch counters: %s", hipGetErrorString(e));
+  rc = run_pipeline(&tmp, st, batch, q, kv, kv_len, node_offsets, d_tree_parent, nullptr, nullptr, attn_out, nullptr, nullptr, 3);
+  if (rc) memcpy(g_init_err, tmp.err, sizeof g_init_err);
+  return rc;
 }
 
 int cb_verify_tree(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, const cb_kv_layer* kv,

@@ -153,3 +153,28 @@ def test_bench_refuses_more_than_one_gpu():
     assert "one GPU" in r.stderr
     assert r.stdout.strip() == ""
 
+
+def test_no_alloc_entry_point_checks_its_arguments_on_the_host():
+    """cb_tree_attention_noalloc rejects bad arguments, and shapes whose scratch need exceeds the library's
+    fixed device array, before it touches a device (so this runs without a GPU; nothing is launched)."""
+    L = B.load()
+    i32 = lambda a: np.ascontiguousarray(a, dtype=np.int32)
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+
+    def call(cfg, kv, kv_len, offs, q=0x10000, out=0x20000, par=0x30000):
+        a, b = i32(kv_len), i32(offs)
+        rc = L.cb_tree_attention_noalloc(C.byref(cfg), None, len(a), q, C.byref(kv), ip(a), ip(b), par, out)
+        return rc, L.cb_last_error(None).decode()
+
+    ragged = B.make_config(32, 32, 128, "bf16", "bf16", 16, 96, 8, 32000, 16, 72)
+    kv = B.CbKvLayer(0x1000, 0x2000, 20000, 0x3000, 1100, 0)
+    lens = [16000 - 700 * b for b in range(16)]
+    offs = np.arange(17) * 96
+    rc, text = call(ragged, kv, lens, offs)                         # the ragged benchmark batch: ~78 MB of partials
+    assert rc == B.CB_ECAP and "scratch" in text, (rc, text)
+    assert call(ragged, kv, lens, offs, q=0)[0] == B.CB_EINVAL       # null pointer
+    assert call(ragged, kv, lens, offs, out=0x20004)[0] == B.CB_EINVAL   # misaligned
+    assert call(ragged, kv, lens[:1] + [-5] + lens[2:], offs)[0] == B.CB_EINVAL
+    assert call(ragged, kv, [17590] * 16, offs)[0] == B.CB_ECAP      # prefix + nodes beyond the block table
+    bad = B.make_config(32, 5, 128, "bf16", "bf16", 1, 64, 6, 100)
+    assert call(bad, kv, [10], [0, 4])[0] == B.CB_EINVAL
