@@ -202,14 +202,22 @@ int cb_compact_kv(cb_ctx *ctx, void *hip_stream, int32_t num_layers, const cb_kv
  *   cb_get_path     host [batch][max_depth+1]: node indices of the accepted path, -1 padded
  *   cb_get_argmax   host [sumN]: first-maximum index of each logits row
  *   cb_device_status  0, or a bit mask: 1 = malformed parent entry seen, 2 = node deeper than max_depth,
- *                     16 = (informational) a split merge had to read partials across XCDs */
+ *                     16 = (informational) a split merge had to read partials across XCDs,
+ *                     32 = (informational) a workgroup of a cooperative merge gave up waiting and left
+ *                     its slice to the workgroup that completed the tile */
 int cb_get_path(cb_ctx *ctx, int32_t *path);
 int cb_get_argmax(cb_ctx *ctx, int32_t *argmax);
 int cb_device_status(cb_ctx *ctx, int32_t *status);
 
-/* Tuning knobs for measurements; unknown names give CB_EINVAL.
+/* ------------------------------------------------------------------------------------------------
+ * Not part of the method: knobs and probes for tests and measurements.  None of them changes what
+ * is computed.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* Options; unknown names give CB_EINVAL.
  *   "splits"     force the number of KV-sequence splits (0 = automatic)
- *   "attn_impl"  0 = automatic, 1 = scalar kernel, 2 = MFMA kernel (bf16, head_dim 128 only)
+ *   "attn_impl"  0 = automatic, 1 = scalar kernel (at most 8 splits on a configuration the MFMA kernel
+ *                takes), 2 = MFMA kernel (bf16, head_dim 128 only)
  *   "stages"     bit mask of the steps cb_verify_tree_device enqueues (1 ancestor sets, 2 attention,
  *                4 argmax, 8 acceptance; default 15) -- for timing one step in isolation; with a
  *                step left out the results of the call are those of an earlier call or undefined
@@ -217,6 +225,14 @@ int cb_device_status(cb_ctx *ctx, int32_t *status);
  *   "fuse_logits"    0 = never run the logits scan and the acceptance inside the attention launch
  *                    (default 1: small calls -- MFMA attention, sequences of at most 64/g nodes, bf16
  *                    logits, no more logits chunks than attention workgroups -- are one launch)
+ *   "coop_merge"     0 = never merge the splits cooperatively (default 1: a grid that fits the
+ *                    machine in one round has every workgroup of a tile merge a slice of it; otherwise,
+ *                    and with 0, the last workgroup of a tile to finish merges it, or a merge kernel)
+ *   "merge_spin_limit"  how often a workgroup of a cooperative merge polls for the tile's other
+ *                    splits before it leaves its slice to the workgroup that completes the tile
+ *                    (default 256; 0 makes every workgroup but the completing one give up at once)
+ *   "external_merge" 1 = always merge with the separate merge kernel
+ *   "timeline"       1 = launch the timeline build of the MFMA kernels (see cb_debug_timestamps)
  *   "time_attention"  1 = record HIP events around the attention kernels (see cb_last_attention_ms) */
 int cb_set_option(cb_ctx *ctx, const char *name, int64_t value);
 
@@ -231,31 +247,17 @@ int cb_last_attention_ms(cb_ctx *ctx, float *ms);
  * CB_ESTATE before the first verify call. */
 int cb_last_launch_info(cb_ctx *ctx, int32_t info[4]);
 
-/* Timing aid: with option "debug_flags" bit 5 (32) set, the MFMA attention kernel stamps eight
- * 100 MHz clock readings per workgroup (entry, arguments read, loads issued, first stage ready,
- * key sweep done, partials written, ticket taken, merge done).  Copies those of the first
- * `workgroups` (<= 1024) workgroups of the last launch to host memory, 8 values each. */
+/* With option "timeline" = 1 the MFMA attention runs in a build that stamps 100 MHz clock readings
+ * per workgroup (entry, arguments read, loads issued, first stage ready, key sweep done, partials
+ * written, merge may start, merge done; eight more for the logits work or the merge's phases).
+ * Copies those of the first `workgroups` (<= 1024) rows of the last launch to host memory, 8 values
+ * each: rows 0..511 the attention's, rows 512.. the second set of workgroups 0..511. */
 int cb_debug_timestamps(cb_ctx *ctx, uint64_t *out, int32_t workgroups);
 
-/* Test hook for an assumption of the MFMA attention kernel, which covers loads to registers and
- * LDS-DMA loads with counted waits of its own: that the two kinds are counted off the wave's
- * vector-memory counter in the order they were requested.  Enqueues probe kernels on the stream
- * (no context needed): `workgroups` x `iters` times a cold load of one kind followed by eight hot
- * loads of the other, a wait that leaves at most those eight in flight, and an immediate look at
- * what the cold load was to bring.  d_cold[i] must hold (uint32)i * 2654435761 + 12345 for
- * i < cold_dwords, with cold_dwords >= workgroups * iters * 4096 + 256; d_hot >= 512 dwords of
- * anything; d_result: 8 zeroed dwords, to which the kernels add the numbers of lane-reads that did
- * not see the loaded value: [0]/[1] register load first, read early / after a full wait; [2]/[3]
- * LDS-DMA first, early / full; [4]/[5] a control that reads the register without waiting (expected
- * to be non-zero: it shows that a violated order would be seen).  All pointers are device memory.
- * CB_EINVAL for bad arguments, CB_EHIP if a launch fails. */
-int cb_probe_load_order(void *hip_stream, const uint32_t *d_cold, int64_t cold_dwords, const uint32_t *d_hot,
-                        int64_t hot_dwords, int32_t workgroups, int32_t iters, uint32_t *d_result);
-
-/* Measurement aid: enqueues a plain streaming read of `bytes` (a multiple of 16, 16-byte aligned)
- * of device memory at d_src -- 1024 workgroups, 16-byte loads, nothing else -- so that a benchmark
- * can time what this machine delivers for a bare read of the size the attention sweeps.  d_sink:
- * 256 dwords of device memory (practically never written).  No context needed. */
+/* Enqueues a plain streaming read of `bytes` (a multiple of 16, 16-byte aligned) of device memory at
+ * d_src -- 1024 workgroups, 16-byte loads, nothing else -- so that a benchmark can time what this
+ * machine delivers for a bare read of the size the attention sweeps.  d_sink: 256 dwords of device
+ * memory (practically never written).  No context needed. */
 int cb_probe_stream_read(void *hip_stream, const void *d_src, int64_t bytes, uint32_t *d_sink);
 
 const char *cb_last_error(const cb_ctx *ctx); /* "" when the last call succeeded; ctx may be NULL

@@ -22,7 +22,7 @@ ERROR_NAMES = {0: "CB_OK", 1: "CB_EINVAL", 2: "CB_ETREE", 3: "CB_ECAP", 4: "CB_E
 
 EXPORTS = ["cb_workspace_bytes", "cb_init", "cb_check_verify_args", "cb_plan_attention", "cb_verify_tree", "cb_verify_tree_device", "cb_tree_attention_device", "cb_tree_attention_noalloc",
            "cb_compact_kv", "cb_get_path", "cb_get_argmax", "cb_device_status", "cb_set_option",
-           "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_probe_load_order", "cb_probe_stream_read", "cb_last_error",
+           "cb_last_launch_info", "cb_last_attention_ms", "cb_debug_timestamps", "cb_probe_stream_read", "cb_last_error",
            "cb_destroy"]
 
 
@@ -77,7 +77,6 @@ def load():
     L.cb_last_launch_info.argtypes = [vp, i32p]
     L.cb_last_attention_ms.argtypes = [vp, C.POINTER(C.c_float)]
     L.cb_debug_timestamps.argtypes = [vp, C.POINTER(C.c_uint64), C.c_int32]
-    L.cb_probe_load_order.argtypes = [vp, vp, C.c_int64, vp, C.c_int64, C.c_int32, C.c_int32, vp]
     L.cb_probe_stream_read.argtypes = [vp, vp, C.c_int64, vp]
     L.cbd_table_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(vp)]
     L.cbd_table_destroy.argtypes = [vp]
@@ -143,18 +142,6 @@ def plan_attention(cfg: CbConfig, kv_len, node_offsets, forced_splits: int = 0) 
     if rc:
         raise CbError(rc, "cb_plan_attention rejected the shape")
     return dict(impl=out[0], nsplit=out[1], chunk=out[2], tile_rows=out[3], workgroups=out[4])
-
-
-def probe_load_order(d_cold, d_hot, workgroups: int, iters: int, d_result, stream=None) -> None:
-    """Enqueue the load-order probe (cb_probe_load_order) on torch tensors: int32 `d_cold` holding the
-    pattern the header names, int32 `d_hot` (>= 512 elements), `d_result` 8 zeroed int32."""
-    import torch
-    st = stream if stream is not None else torch.cuda.current_stream()
-    rc = load().cb_probe_load_order(C.c_void_p(st.cuda_stream), C.c_void_p(d_cold.data_ptr()), d_cold.numel(),
-                                    C.c_void_p(d_hot.data_ptr()), d_hot.numel(), workgroups, iters,
-                                    C.c_void_p(d_result.data_ptr()))
-    if rc:
-        raise CbError(rc, "cb_probe_load_order rejected the arguments")
 
 
 def probe_stream_read(d_src, nbytes: int, d_sink, stream=None) -> None:

@@ -59,7 +59,8 @@ def untracked_load_violations(asm: str) -> list:
         if "ASMEND" in line:
             in_asm = False
             continue
-        m = re.search(r"global_load_dwordx4 v\[(\d+):(\d+)\]", line) if in_asm else None
+        # (every register-returning load spelling: the query rows' and the logits item's 16-byte loads today)
+        m = re.search(r"(?:global|buffer|flat)_load_dword(?:x[234])? v\[(\d+):(\d+)\]", line) if in_asm else None
         if not m:
             continue
         lo, hi = int(m.group(1)), int(m.group(2))

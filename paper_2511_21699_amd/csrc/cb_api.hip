@@ -134,7 +134,7 @@ struct cb_ctx {
   int32_t last_len[CB_MAX_BATCH];
   hipStream_t last_stream;
   // options
-  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_debug, opt_fork, opt_fuse, opt_coop, opt_spin;
+  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_timeline, opt_external, opt_fork, opt_fuse, opt_coop, opt_spin;
   hipEvent_t ev0, ev1, ev_fork, ev_join;
   hipStream_t aux;  // second stream (default priority) for the logits scan beside the attention
   bool ev_valid;
@@ -320,7 +320,8 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   ap.scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
   ap.status = ctx->dev<int32_t>(ctx->lay.status);
   ap.dbg_ts = ctx->dev<unsigned long long>(ctx->lay.dbg);
-  ap.debug_flags = (int32_t)ctx->opt_debug;
+  ap.timeline = ctx->opt_timeline ? 1 : 0;
+  ap.force_external_merge = ctx->opt_external ? 1 : 0;
   ap.max_depth = c.max_depth;
   ap.coop_merge = ctx->opt_coop ? 0 : -1;
   ap.spin_limit = (int32_t)ctx->opt_spin;
@@ -784,7 +785,8 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   else if (!strcmp(name, "attn_impl")) ctx->opt_impl = value;
   else if (!strcmp(name, "time_attention")) ctx->opt_time = value;
   else if (!strcmp(name, "stages")) ctx->opt_stages = value & 15;
-  else if (!strcmp(name, "debug_flags")) ctx->opt_debug = value;
+  else if (!strcmp(name, "timeline")) ctx->opt_timeline = value;
+  else if (!strcmp(name, "external_merge")) ctx->opt_external = value;
   else if (!strcmp(name, "parallel_scan")) ctx->opt_fork = value;
   else if (!strcmp(name, "fuse_logits")) ctx->opt_fuse = value;
   else if (!strcmp(name, "coop_merge")) ctx->opt_coop = value;

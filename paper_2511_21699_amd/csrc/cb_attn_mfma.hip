@@ -396,7 +396,7 @@ __device__ __forceinline__ void pin_args(AttnParams& p) {
   CB_PIN(p.kv.seq_stride); CB_PIN(p.kv.token_stride); CB_PIN(p.kv.head_stride); CB_PIN(p.kv.num_blocks);
   CB_PIN(p.kv.max_blocks); CB_PIN(p.kv.block_size); CB_PIN(p.parent); CB_PIN(p.partial); CB_PIN(p.tickets); CB_PIN(p.coop_tickets);
   CB_PIN(p.Hq); CB_PIN(p.Hkv); CB_PIN(p.chunk); CB_PIN(p.nsplit); CB_PIN(p.batch); CB_PIN(p.scale);
-  CB_PIN(p.external_merge); CB_PIN(p.max_depth); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.debug_flags); CB_PIN(p.coop_merge); CB_PIN(p.spin_limit);
+  CB_PIN(p.external_merge); CB_PIN(p.max_depth); CB_PIN(p.xcd_remap); CB_PIN(p.grid_x); CB_PIN(p.grid_y); CB_PIN(p.grid_z); CB_PIN(p.coop_merge); CB_PIN(p.spin_limit);
   CB_PIN(p.status); CB_PIN(p.dbg_ts);
 }
 __device__ __forceinline__ void pin_logits_args(LogitsWork& w) {
@@ -490,7 +490,7 @@ __device__ __forceinline__ void merge_tile(__amdgpu_buffer_rsrc_t prsrc, const i
 // `hook` (FUSE only) is the workgroup's share of the logits work; with one row tile per wave there
 // are registers to spare and its item is woven into the attention's own waits and barriers (see
 // LogitsHook).
-template <int R, int G, bool SEQ, bool FUSE>
+template <int R, int G, bool SEQ, bool FUSE, bool TS>
 __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMetaLanes& ml, unsigned long long ts0,
                                           LogitsHook<256 * G>* hook, unsigned long long* ts_sh) {
   constexpr bool kHookEarly = FUSE && R == 1;
@@ -551,8 +551,10 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   // here, even one that never executes, makes the compiler treat the loads in flight as unordered
   // and wait for all of them wherever it needs one)
   CB_LDS unsigned long long* ts = (CB_LDS unsigned long long*)ts_sh;
-  const bool do_ts = (p.debug_flags & 32) && threadIdx.x == 0 && wg_linear < 1024;
-  const bool do_ts64 = (p.debug_flags & 32) && threadIdx.x == 64 && wg_linear < 1024;
+  // (TS: the timeline build of the kernel, a measurement aid; every stamp below is compiled out of the
+  // kernels that ship as the default)
+  const bool do_ts = TS && threadIdx.x == 0 && wg_linear < 1024;
+  const bool do_ts64 = TS && threadIdx.x == 64 && wg_linear < 1024;
 #define CB_TS(i) do { if (do_ts) ts[i] = wall_clock64(); } while (0)
   if (do_ts) {
 #pragma unroll
@@ -635,8 +637,6 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
     uint4* const base = ring + slot * (2 * kStageVecs);
     issue_half(base, base + kStageVecs, ka, kbase, vbase, k0 + h * kStageKeys, last_key, w, l);
   };
-  const bool fine_ts = (p.debug_flags & 1024) != 0;  // (timing aid: slots 5-7 stamp the issue phase instead)
-  if (fine_ts) CB_TS(5);
   // The prologue requests PRO half-stages, and the rest of the ring goes out right behind the
   // first stage's barrier -- all unconditionally (requests past the split's end repeat its last
   // key and are never used), so every wave has a known number of requests behind its query loads,
@@ -647,8 +647,6 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 #pragma unroll
   for (int h = 0; h < PRO; h++) {
     issue(h, h);
-    if (fine_ts && h == 1) CB_TS(6);
-    if (fine_ts && h == 3) CB_TS(7);
   }
   CB_TS(2);
   if (tree_split) build_ancestor_sets(anc_sh, N, my_parent, jump_rounds(p.max_depth));  // uniform in the workgroup; hidden behind the first K/V wait
@@ -721,7 +719,6 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 
   wait_vmcnt<0>();  // (a short split: the unused rest of the prologue must land before the ring is reused)
   CB_TS(4);
-  if (p.debug_flags & 8) return;  // (timing aid: stop after the key sweep)
   if constexpr (kHookEarly) {
     hook->scan_first();  // its store completes together with the partials' stores below
     hook->stamp(2);
@@ -815,14 +812,14 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
           const int dt = dt0 + i;
           const uintx2 v = {(uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16),
                             (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16)};
-          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + dt * 512 + l * 8, 0, 0);
+          if (p.external_merge) __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + dt * 512 + l * 8, 0, 0);
           else __builtin_amdgcn_raw_buffer_store_b64(v, prsrc, pbyte + dt * 512 + l * 8, 0, kAgentCoherent);
         }
         if (kg == 0 && (!kTwoGroups || gi == 0)) {
           // m = log2 of the reference weight 2^(c2*mref)
           const float mnat = (st.mref[rr] == -INFINITY) ? -INFINITY : st.mref[rr] * c2;  // log2 units
           const uintx2 ml = {__float_as_uint(mnat), __float_as_uint(lt)};
-          if (p.external_merge || (p.debug_flags & 512)) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + kUnitMl + c * 8, 0, 0);
+          if (p.external_merge) __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + kUnitMl + c * 8, 0, 0);
           else __builtin_amdgcn_raw_buffer_store_b64(ml, prsrc, pbyte + kUnitMl + c * 8, 0, kAgentCoherent);
         }
       }
@@ -1015,12 +1012,14 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
 #undef CB_TS
 }
 
-// Timing aid (debug bit 5): thread 0 copies the workgroup's stamps from LDS to the table, the
+// Timing aid (timeline build): thread 0 copies the workgroup's stamps from LDS to the table, the
 // attention's eight to row wg, the logits hook's eight to row wg + 512.
+template <bool TS>
 __device__ __forceinline__ void flush_timestamps(const AttnParams& p, const unsigned long long* ts_sh, bool hook_rows) {
+  if constexpr (!TS) return;
   const int wg = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
-  if (p.debug_flags & 32) __syncthreads();  // (thread 64 stamps too)
-  if (!(p.debug_flags & 32) || threadIdx.x != 0 || wg >= 1024) return;
+  __syncthreads();  // (thread 64 stamps too)
+  if (threadIdx.x != 0 || wg >= 1024) return;
   const CB_LDS unsigned long long* ts = (const CB_LDS unsigned long long*)ts_sh;
   CB_GLOBAL unsigned long long* out = (CB_GLOBAL unsigned long long*)p.dbg_ts;
   for (int i = 0; i < 8; i++) out[(int64_t)wg * 8 + i] = ts[i];
@@ -1028,13 +1027,13 @@ __device__ __forceinline__ void flush_timestamps(const AttnParams& p, const unsi
     for (int i = 0; i < 8; i++) out[(int64_t)(wg + 512) * 8 + i] = ts[8 + i];
 }
 
-template <int R, int G, bool SEQ>
+template <int R, int G, bool SEQ, bool TS>
 __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p, SeqMeta meta) {
-  const unsigned long long ts0 = wall_clock64();
+  const unsigned long long ts0 = TS ? wall_clock64() : 0ull;
   const SeqMetaLanes ml = seq_meta_prefetch(meta);
-  __shared__ unsigned long long ts_sh[16];
-  attn_tile<R, G, SEQ, false>(p, ml, ts0, nullptr, ts_sh);
-  flush_timestamps(p, ts_sh, true);
+  __shared__ unsigned long long ts_sh[TS ? 16 : 1];
+  attn_tile<R, G, SEQ, false, TS>(p, ml, ts0, nullptr, ts_sh);
+  flush_timestamps<TS>(p, ts_sh, true);
 }
 
 // The whole verification in one launch: every workgroup does its attention duty (a tile's split,
@@ -1042,20 +1041,20 @@ __global__ __launch_bounds__(256 * G) void k_attn_mfma(AttnParams p, SeqMeta met
 // sequence's scan runs the sequence's acceptance (LogitsHook of cb_logits.h).  The scan does not
 // depend on the attention, so it needs no ordering against it, and its memory round trips ride on
 // those the attention needs anyway.
-template <int R, int G, bool SEQ>
+template <int R, int G, bool SEQ, bool TS>
 __global__ __launch_bounds__(256 * G) void k_verify_mfma(AttnParams p, SeqMeta meta, LogitsWork lw_arg) {
-  const unsigned long long ts0 = wall_clock64();
+  const unsigned long long ts0 = TS ? wall_clock64() : 0ull;
   const SeqMetaLanes ml = seq_meta_prefetch(meta);
   LogitsWork lw = lw_arg;
   pin_logits_args(lw);  // fetched with the attention's arguments, not later in front of the first use
   __shared__ TailLds tail;
   const int wg = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
   LogitsHook<256 * G> hook(lw, ml, tail, wg);
-  __shared__ unsigned long long ts_sh[16];
-  if (p.debug_flags & 32) hook.dbg = (CB_LDS unsigned long long*)ts_sh + 8;  // (timing aid)
-  attn_tile<R, G, SEQ, true>(p, ml, ts0, &hook, ts_sh);
+  __shared__ unsigned long long ts_sh[TS ? 16 : 1];
+  if constexpr (TS) hook.dbg = (CB_LDS unsigned long long*)ts_sh + 8;  // (timing aid)
+  attn_tile<R, G, SEQ, true, TS>(p, ml, ts0, &hook, ts_sh);
   hook.finish();
-  flush_timestamps(p, ts_sh, true);
+  flush_timestamps<TS>(p, ts_sh, true);
 }
 
 // Stand-alone merge of the bf16 partials, used when a tile's partials are too many for one
@@ -1157,7 +1156,7 @@ int attn_mfma_tile_rows(int mrows) { return mrows <= 64 ? 64 : (mrows <= 128 ? 1
 // than workgroups, bf16 logits.  Larger calls run in several rounds of workgroups, where a
 // stand-alone scan at full occupancy is faster.
 bool attn_mfma_can_fuse(const AttnParams& p, int max_nodes_in_call, int64_t logits_items, int logits_dtype) {
-  if (!attn_mfma_supports(p) || (p.debug_flags & (64 | 128)) || logits_dtype != CB_BF16) return false;
+  if (!attn_mfma_supports(p) || logits_dtype != CB_BF16) return false;
   const int M = max_nodes_in_call * (p.Hq / p.Hkv);
   if (attn_mfma_tile_rows(M) != 64) return false;
   const int64_t T = (int64_t)p.nsplit * p.Hkv * p.batch;
@@ -1169,9 +1168,7 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   if (!attn_mfma_supports(p)) return hipErrorInvalidValue;
   const int g = p.Hq / p.Hkv;
   const int M = max_nodes_in_call * g;
-  int rt_rows = attn_mfma_tile_rows(M);
-  if ((p.debug_flags & 64) && rt_rows > 128) rt_rows = 128;  // (timing aids: smaller row tiles)
-  if (p.debug_flags & 128) rt_rows = 64;
+  const int rt_rows = attn_mfma_tile_rows(M);
   const int tiles = (M + rt_rows - 1) / rt_rows;
   dim3 grid(p.nsplit, p.Hkv * tiles, p.batch);
   AttnParams q = p;
@@ -1196,19 +1193,29 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   q.coop_merge = (p.coop_merge >= 0 && p.coop_tickets && p.nsplit > 1 && p.nsplit <= 64 && compute_units > 0 && T <= compute_units &&
                   (int64_t)p.Hkv * tiles * p.batch <= kCoopTiles) ? 1 : 0;
   if (q.coop_merge) q.external_merge = 0;
-  if (p.debug_flags & 256) { q.external_merge = 1; q.coop_merge = 0; }  // (timing aid)
+  if (p.force_external_merge && p.nsplit > 1) { q.external_merge = 1; q.coop_merge = 0; }  // (option "external_merge": a test aid)
+  const bool ts = p.timeline != 0;  // (the timeline build of the same kernels: a measurement aid)
+#define CB_LAUNCH_ATTN(R, G, SEQ)                                                                           \
+  do {                                                                                                      \
+    if (ts) hipLaunchKernelGGL((k_attn_mfma<R, G, SEQ, true>), grid, dim3(256 * G), 0, st, q, meta);        \
+    else hipLaunchKernelGGL((k_attn_mfma<R, G, SEQ, false>), grid, dim3(256 * G), 0, st, q, meta);          \
+  } while (0)
   if (logits_work) {
     const LogitsWork& lw = *logits_work;
     if (!attn_mfma_can_fuse(p, max_nodes_in_call, (int64_t)lw.rows * lw.accept.nchunks, CB_BF16)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_verify_mfma<1, 2, false>), grid, dim3(512), 0, st, q, meta, lw);
+    if (ts) hipLaunchKernelGGL((k_verify_mfma<1, 2, false, true>), grid, dim3(512), 0, st, q, meta, lw);
+    else hipLaunchKernelGGL((k_verify_mfma<1, 2, false, false>), grid, dim3(512), 0, st, q, meta, lw);
+  } else if (rt_rows == 64) {
+    CB_LAUNCH_ATTN(1, 2, false);
+  } else if (rt_rows == 128) {
+    CB_LAUNCH_ATTN(2, 2, false);
   } else {
-    if (rt_rows == 64) hipLaunchKernelGGL((k_attn_mfma<1, 2, false>), grid, dim3(512), 0, st, q, meta);
-    else if (rt_rows == 128) hipLaunchKernelGGL((k_attn_mfma<2, 2, false>), grid, dim3(512), 0, st, q, meta);
-    else hipLaunchKernelGGL((k_attn_mfma<2, 2, true>), grid, dim3(512), 0, st, q, meta);
+    CB_LAUNCH_ATTN(2, 2, true);
   }
+#undef CB_LAUNCH_ATTN
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (q.external_merge && !(p.debug_flags & 1)) {
+  if (q.external_merge) {
     const int tiles16 = (M + 15) / 16;
     hipLaunchKernelGGL(k_merge_partials_bf16, dim3(tiles16, p.Hkv, p.batch), dim3(256), 0, st, q, meta);
     e = hipGetLastError();

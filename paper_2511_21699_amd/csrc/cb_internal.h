@@ -168,9 +168,10 @@ struct AttnParams {
                            // (set by the launcher when the grid is resident in one round); -1 on input: never
   int32_t spin_limit;      // cooperative merge: polls of the tile's ticket before a workgroup gives up
   int32_t max_depth;    // deepest node the configuration allows (bounds the ancestor-set rounds)
-  int32_t debug_flags;  // bit 0: skip the split merge (timing aid; output then undefined)
+  int32_t timeline;     // 1: launch the timeline build of the kernel (stamps per workgroup in dbg_ts; a measurement aid)
+  int32_t force_external_merge;  // 1: always merge with the separate kernel (a test aid)
   int32_t* status;      // device status word (bit 4: a merge had to use cross-XCD loads)
-  unsigned long long* dbg_ts;  // timing aid: 8 timestamps (100 MHz) per workgroup when debug bit 5 is set
+  unsigned long long* dbg_ts;  // timeline build: 8 timestamps (100 MHz) per workgroup, 1024 rows
 };
 
 struct ArgmaxPartial {

@@ -39,8 +39,28 @@ def sample_rows(case, count: int, seed: int = 0) -> np.ndarray:
     return np.asarray(rows, dtype=np.int32)
 
 
+def structured_rows(case, per_tile: int = 1) -> np.ndarray:
+    """(sequence, head, node) triples that put `per_tile` rows into every 16-row tile of every kv head of
+    every sequence -- the unit a wavefront of the MFMA kernel owns -- at a row position that walks through
+    the tile with the tile and head numbers.  The kernel's rows of one kv head are node * g + (head % g);
+    every workgroup row tile (64, 128 or 256 rows) and every wave inside it is a union of such 16-row
+    tiles, and every row attends to the whole prefix, i.e. takes a contribution from every split."""
+    g = case.Hq // case.Hkv
+    rows = []
+    for b in range(case.B):
+        n = int(case.node_offsets[b + 1] - case.node_offsets[b])
+        m = n * g
+        for hk in range(case.Hkv):
+            for t in range((m + 15) // 16):
+                for j in range(per_tile):
+                    r = t * 16 + (t + hk + 5 * j + 3 * b) % 16
+                    r = min(r, m - 1)
+                    rows.append((b, hk * g + r % g, r // g))
+    return np.asarray(sorted(set(rows)), dtype=np.int32)
+
+
 def run_case(case, rows=None, layout=B.CB_LAYOUT_TOKEN_MAJOR, options=None, max_splits=0, compact=True,
-             threads=16, what=""):
+             threads=16, what="", expect_status=0):
     """Full parity run.  ``rows`` = None checks every attention row, else the sampled triples."""
     import torch
     print(f"[case] {what or case.name} dtype={case.dtype} B={case.B} Hq={case.Hq} Hkv={case.Hkv} D={case.D} "
@@ -54,7 +74,9 @@ def run_case(case, rows=None, layout=B.CB_LAYOUT_TOKEN_MAJOR, options=None, max_
         out, acc_len, acc_tok = ver.verify_tree(dc.q, dc.kv, case.kv_len, case.node_offsets, case.parent,
                                                 case.tokens, dc.logits)
         torch.cuda.synchronize()
-        assert ver.device_status() & 3 == 0      # bits 0-1: tree problems; bit 4 only reports a cross-XCD merge
+        status = ver.device_status()
+        assert status & 3 == 0                   # bits 0-1: tree problems; bits 4 and 5 only report how a merge went
+        assert status & expect_status == expect_status, f"{what}: device status {status}, expected bits {expect_status}"
         # ---- argmax / acceptance: bit-exact
         a_ref, res = O.verify(case)
         a_gpu = ver.get_argmax(case.total_nodes)

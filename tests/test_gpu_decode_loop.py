@@ -50,11 +50,21 @@ def test_dual_tables_beat_either_table_alone_on_a_text_with_shared_phrases():
     """Section 3.3 / Table 1 of the paper, on a synthetic language: the frozen table (built from a corpus
     sample, Section 4) knows the shared phrases, the dynamic one the text's own repetitions; drafting from
     both accepts more tokens per step than drafting from either."""
+    from oracle import cb_oracle as O
+    checked = []
+
+    def check(step, parent, token, logits_rows, emitted):      # every step's acceptance against the oracle
+        a = O.argmax(B.to_host(logits_rows, "bf16"), "bf16")
+        L, path, toks = O.accept(parent, token, a)
+        assert emitted.tolist() == toks.tolist(), f"step {step}: GPU {emitted.tolist()} oracle {toks.tolist()}"
+        checked.append(L)
+
     kw = dict(steps=250, node_budget=48, prompt_len=600, Hq=4, Hkv=4, vocab=8000, lc=4096, seed=13, warmup=0,
-              corpus_tokens=60000)
+              corpus_tokens=60000, check_with=check)
     dual = decode_loop.run(tables="dual", **kw)
     dyn = decode_loop.run(tables="dual", use_only="dynamic", **kw)
     frz = decode_loop.run(tables="frozen", **kw)
+    assert len(checked) == 750
     assert dual["lossless"] and dyn["lossless"] and frz["lossless"]
     assert dual["mean_accepted_tokens_per_step"] > dyn["mean_accepted_tokens_per_step"] + 0.1
     assert dual["mean_accepted_tokens_per_step"] > frz["mean_accepted_tokens_per_step"] + 0.1

@@ -6,7 +6,7 @@ import pytest
 
 from paper_2511_21699_amd import binding as B
 from paper_2511_21699_amd import workloads as W
-from tests.gpu_harness import check_attention, run_case, sample_rows
+from tests.gpu_harness import check_attention, run_case, sample_rows, structured_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -48,19 +48,29 @@ def test_config5_long_reduced(impl):
 
 
 # ---------------------------------------------------------------- full sizes, sampled rows
+# (rows in every 16-row tile of every kv head -- every workgroup row tile and every wave of it -- and
+# each of them attends to the whole prefix, so every split, the first, the last and the one that
+# reaches the tree, contributes to every checked row)
 def test_config3_gqa_full_size_sampled():
     case = W.make_config(3)
-    run_case(case, rows=sample_rows(case, 256), what="cfg3 full")
+    rows = structured_rows(case, per_tile=2)
+    assert len(rows) >= 512
+    run_case(case, rows=rows, what="cfg3 full")
 
 
 def test_config4_ragged_full_size_sampled():
     case = W.make_config(4)
-    run_case(case, rows=sample_rows(case, 160), max_splits=72, what="cfg4 full")
+    rows = structured_rows(case)[::4]          # every fourth (tile, head) pair: still every sequence, head and tile index
+    rows = np.concatenate([rows, sample_rows(case, 64)])
+    assert len(rows) >= 512
+    run_case(case, rows=rows, max_splits=72, what="cfg4 full")
 
 
 def test_config5_long_full_size_sampled():
     case = W.make_config(5)
-    run_case(case, rows=sample_rows(case, 48), what="cfg5 full")
+    rows = structured_rows(case)
+    assert len(rows) >= 512
+    run_case(case, rows=rows, what="cfg5 full")
 
 
 # ---------------------------------------------------------------- edge cases
@@ -83,12 +93,32 @@ def test_ragged_prefix_lengths_around_tile_edges(S):
     run_case(W.custom_case(40 + S, "bf16", 1, 4, 2, 128, 1000, [S], [par], q_scale=3.0), what=f"S={S}")
 
 
+@pytest.mark.parametrize("merge", ["cooperative", "last_arrival", "merge_kernel", "gave_up"])
 @pytest.mark.parametrize("splits", [1, 2, 5, 13])
-def test_split_counts_agree_with_the_oracle(splits):
+def test_split_counts_agree_with_the_oracle(splits, merge):
+    """Every way the splits of a tile can be merged: cooperatively by the tile's workgroups (the default when
+    the grid fits the machine in one round), by the last workgroup to finish, by the separate merge kernel,
+    and cooperatively with a spin limit of zero -- every workgroup but the one that completes a tile gives up
+    at once and leaves its slice to that one (status bit 32 says that it happened)."""
     rng = np.random.default_rng(5)
     par = W.random_tree(rng, 64, 4, 6, False)[0]
     case = W.custom_case(50, "bf16", 1, 8, 8, 128, 1000, [1000], [par], q_scale=2.0)
-    run_case(case, options={"splits": splits}, what=f"splits={splits}")
+    opts = {"cooperative": {}, "last_arrival": {"coop_merge": 0}, "merge_kernel": {"external_merge": 1},
+            "gave_up": {"merge_spin_limit": 0}}[merge]
+    run_case(case, options=dict(opts, splits=splits), what=f"splits={splits} merge={merge}",
+             expect_status=32 if (merge == "gave_up" and splits > 1) else 0)
+
+
+@pytest.mark.parametrize("opts", [{}, {"coop_merge": 0}, {"fuse_logits": 0}, {"fuse_logits": 0, "coop_merge": 0}])
+def test_merge_across_xcds(opts):
+    """15 workgroups (3 kv heads x 5 splits) cannot be renumbered into whole tiles per XCD, so the splits of a
+    tile run on different XCDs and the merge must read the partials past its own L2: the device status word
+    reports that branch (bit 16), and the results are the oracle's -- for the cooperative merge, the
+    last-arrival merge, and the one-launch verification's acceptance behind either."""
+    rng = np.random.default_rng(15)
+    par = W.random_tree(rng, 12, 3, 4, False)[0]          # 12 logits items for 15 workgroups: small enough for one launch
+    case = W.custom_case(55, "bf16", 1, 3, 3, 128, 8000, [1100], [par], q_scale=2.0, p_match=0.8)
+    run_case(case, options=dict(opts, splits=5), what=f"cross-XCD merge {opts}", expect_status=16)
 
 
 @pytest.mark.parametrize("layout", [B.CB_LAYOUT_TOKEN_MAJOR, B.CB_LAYOUT_HEAD_MAJOR])
@@ -254,6 +284,60 @@ def test_hip_graph_replays_match_eager_steps(S):
         assert np.array_equal(k0, k_ref) and np.array_equal(v0, v_ref)
 
 
+def test_one_graph_of_different_cases_through_one_workspace():
+    """Three different verification steps -- different trees, prefix lengths, queries, logits -- captured
+    back to back into one HIP graph through ONE context, so they share the workspace (split partials, merge
+    and scan tickets, argmax partials), replayed three times with eager work between the replays.  Every
+    step of every replay is checked against the oracle: a stale partial, or a ticket that one step left
+    behind for the next, would show here.  The caches evolve (each step compacts its accepted path), and the
+    oracle's copies evolve with them."""
+    import copy
+    import torch
+    from oracle import cb_oracle as O
+    rng = np.random.default_rng(41)
+    cases = [W.make_config(2),
+             W.custom_case(411, "bf16", 1, 32, 32, 128, 32000, [1500], [W.random_tree(rng, 40, 4, 6, False)[0]], p_match=0.8),
+             W.custom_case(412, "bf16", 1, 32, 32, 128, 32000, [333], [W.random_tree(rng, 64, 3, 6, False)[0]], q_scale=2.0, p_match=0.7)]
+    depth = max(c.max_depth for c in cases)
+    cfg = B.make_config(32, 32, 128, "bf16", "bf16", 1, 64, depth, 32000)
+    ver = B.Verifier(cfg)
+    side = torch.cuda.Stream()
+    dcs = [B.DeviceCase(c) for c in cases]
+    pars = [torch.from_numpy(c.parent).cuda() for c in cases]
+    toks = [torch.from_numpy(c.tokens).cuda() for c in cases]
+    outs = [torch.zeros_like(dc.q) for dc in dcs]
+    lens = [torch.zeros(1, dtype=torch.int32, device="cuda") for _ in cases]
+    accs = [torch.zeros(1, depth + 1, dtype=torch.int32, device="cuda") for _ in cases]
+    steps = [ver.bind_step(dc.q, dc.kv, c.kv_len, c.node_offsets, pars[i], toks[i], dc.logits, outs[i], lens[i], accs[i],
+                           [dc.kv], stream=side) for i, (c, dc) in enumerate(zip(cases, dcs))]
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for st in steps:
+                st()
+    refs = [copy.copy(c) for c in cases]
+    for r in refs:
+        r.k, r.v = r.k.copy(), r.v.copy()
+    for rep in range(3):
+        with torch.cuda.stream(side):
+            graph.replay()
+        side.synchronize()
+        scratch = sum(float(o.float().abs().sum()) for o in outs)     # eager work of the program's own between replays
+        assert np.isfinite(scratch)
+        for i, (c, ref) in enumerate(zip(cases, refs)):
+            print(f"[case] shared-workspace graph: replay {rep} step {i}", flush=True)
+            a_ref, res = O.verify(ref)
+            L, path, tk = res[0]
+            assert int(lens[i].item()) == L, f"replay {rep} step {i}: accepted_len"
+            assert accs[i][0, :L + 1].cpu().tolist() == tk.tolist(), f"replay {rep} step {i}: accepted tokens"
+            check_attention(ref, W.to_f64(B.to_host(outs[i], "bf16"), "bf16"), O.attention(ref), f"replay {rep} step {i}")
+            O.compact(ref, ref.k, ref.v, 0, path)
+            assert np.array_equal(B.to_host(dcs[i].k, "bf16"), ref.k) and np.array_equal(B.to_host(dcs[i].v, "bf16"), ref.v), \
+                f"replay {rep} step {i}: compacted cache"
+    assert ver.device_status() & 3 == 0
+    ver.close()
+
+
 @pytest.mark.parametrize("shape", ["7b", "ragged", "odd_vocab", "single_nodes", "many_splits"])
 def test_one_launch_verification_matches_separate_launches(shape):
     """Small calls run attention, logits scan and acceptance as one launch; the same call with that
@@ -338,8 +422,28 @@ def test_model_step_of_several_layers(kind):
     d_acc = torch.zeros(2, case.max_depth + 1, dtype=torch.int32, device="cuda")
     step = ver.bind_model_step([dc.q for dc in dcs], kvs, case.kv_len, case.node_offsets, d_par, d_tok, dcs[-1].logits,
                                outs, d_len, d_acc)
+    # the same step captured as one HIP graph (what `bench.py --layers` replays) on copies of the caches:
+    # after one replay it must have left exactly what the eager step leaves
+    dcs2 = [B.DeviceCase(c) for c in layers]
+    kvs2 = [B.kv_layer(dc.k, dc.v, dcs[0].block_table, paged=case.block_size > 0) for dc in dcs2]
+    outs2 = [torch.zeros_like(dc.q) for dc in dcs2]
+    d_len2 = torch.zeros(2, dtype=torch.int32, device="cuda")
+    d_acc2 = torch.zeros(2, case.max_depth + 1, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    step2 = ver.bind_model_step([dc.q for dc in dcs2], kvs2, case.kv_len, case.node_offsets, d_par, d_tok, dcs2[-1].logits,
+                                outs2, d_len2, d_acc2, stream=side)
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step2()
     step()
     torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        graph.replay()
+    side.synchronize()
+    assert torch.equal(d_len, d_len2) and torch.equal(d_acc, d_acc2)
+    for o1, o2, a, b2 in zip(outs, outs2, dcs, dcs2):
+        assert torch.equal(o1, o2) and torch.equal(a.k, b2.k) and torch.equal(a.v, b2.v), "graph replay of the model step differs from the eager step"
     assert ver.device_status() & 3 == 0
     a_ref, res = O.verify(layers[-1])
     assert d_len.cpu().tolist() == [r[0] for r in res]
