@@ -243,9 +243,11 @@ int cb_last_attention_ms(cb_ctx *ctx, float *ms);
 
 /* How the last verify call was launched (host memory, no device access): info[0] = attention kernel
  * family (1 scalar, 2 MFMA), info[1] = partial slots per output row, info[2] = keys per split,
- * info[3] = 1 if the logits scan and the acceptance ran inside the attention launch, else 0.
- * CB_ESTATE before the first verify call. */
-int cb_last_launch_info(cb_ctx *ctx, int32_t info[4]);
+ * info[3] = 1 if the logits scan and the acceptance ran inside the attention launch, else 0,
+ * info[4] = how the splits were merged (0 one split, 1 cooperatively by the tile's workgroups, 2 by the
+ * last workgroup of a tile to finish, 3 by a separate merge kernel), info[5] = kernels the call
+ * enqueued.  CB_ESTATE before the first verify call. */
+int cb_last_launch_info(cb_ctx *ctx, int32_t info[6]);
 
 /* With option "timeline" = 1 the MFMA attention runs in a build that stamps 100 MHz clock readings
  * per workgroup (entry, arguments read, loads issued, first stage ready, key sweep done, partials

@@ -325,9 +325,10 @@ class Verifier:
         return out
 
     def last_launch_info(self) -> dict:
-        out = (C.c_int32 * 4)()
+        out = (C.c_int32 * 6)()
         self._raise(self.L.cb_last_launch_info(self.ctx, out))
-        return dict(impl=out[0], nsplit=out[1], chunk=out[2], fused=bool(out[3]))
+        return dict(impl=out[0], nsplit=out[1], chunk=out[2], fused=bool(out[3]),
+                    merge=("none", "cooperative", "last_arrival", "merge_kernel")[out[4]], kernels=out[5])
 
     def last_attention_ms(self) -> float:
         ms = C.c_float(0)

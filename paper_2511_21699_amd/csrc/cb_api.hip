@@ -126,7 +126,7 @@ struct cb_ctx {
   void* h_block;
   // state of the last verify
   bool have_verify;
-  int32_t launch_info[4];
+  int32_t launch_info[6];
   bool host_knows_len;
   int batch;
   int total_nodes;
@@ -356,6 +356,7 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
                      attn_mfma_can_fuse(ap, plan.max_nodes, (int64_t)total * ctx->lay.amax_chunks, c.logits_dtype);
   const bool fork = !fused && ctx->opt_fork != 0 && use_mfma && (stages & 2) && (stages & 4);
   hipStream_t scan_stream = st;
+  int merge_kind = plan.nsplit > 1 ? 3 : 0, kernels = 0;  // (the scalar attention always merges with a kernel of its own)
   if (fork) {
     CB_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
     CB_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->ev_fork, 0));
@@ -368,9 +369,11 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
                               ctx->dev<ArgmaxPartial>(ctx->lay.amax_partial), ctx->lay.amax_chunks, batch, meta,
                               carry ? d_parent : nullptr, c.max_depth, carry ? ctx->dev<uint32_t>(ctx->lay.anc) : nullptr,
                               carry ? ctx->dev<int32_t>(ctx->lay.status) : nullptr));
+    kernels++;
   } else if (!use_mfma && (stages & 1)) {
     CB_LAUNCH(ctx, launch_tree_prepare(st, batch, meta, d_parent, c.max_depth, ctx->dev<uint32_t>(ctx->lay.anc),
                                     ctx->dev<int32_t>(ctx->lay.status)));
+    kernels++;
   }
   if (fork) CB_HIP(ctx, hipEventRecord(ctx->ev_join, ctx->aux));
   const bool timing = ctx->opt_time != 0;
@@ -387,22 +390,29 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
     lw.accept.partial = ctx->dev<ArgmaxPartial>(ctx->lay.amax_lines);
     lw.accept.slot_stride = 16;
     lw.partial_out = ctx->dev<ArgmaxPartial>(ctx->lay.amax_lines);
-    CB_LAUNCH(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total, fused ? &lw : nullptr));  // merges its own splits
+    CB_LAUNCH(ctx, launch_attn_mfma(st, ap, meta, plan.max_nodes, total, fused ? &lw : nullptr, &merge_kind));  // merges its own splits
+    kernels += merge_kind == 3 ? 2 : 1;
   } else {
     CB_LAUNCH(ctx, launch_attn_simt(st, ap, meta, c.qkv_dtype, plan.max_nodes));
     if (plan.nsplit > 1) CB_LAUNCH(ctx, launch_merge(st, ap, meta, c.qkv_dtype, total));
+    kernels += plan.nsplit > 1 ? 2 : 1;
   }
   if (timing) {
     CB_HIP(ctx, hipEventRecord(ctx->ev1, st));
     ctx->ev_valid = true;
   }
   if (fork) CB_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
-  if ((stages & 8) && !fused) CB_LAUNCH(ctx, launch_accept(st, batch, meta, acc));
+  if ((stages & 8) && !fused) {
+    CB_LAUNCH(ctx, launch_accept(st, batch, meta, acc));
+    kernels++;
+  }
   if (!(stage_mask & 8)) return CB_OK;  // attention alone leaves the state of the last verification as it is
   ctx->launch_info[0] = use_mfma ? 2 : 1;
   ctx->launch_info[1] = plan.nsplit;
   ctx->launch_info[2] = plan.chunk;
   ctx->launch_info[3] = fused ? 1 : 0;
+  ctx->launch_info[4] = merge_kind;
+  ctx->launch_info[5] = kernels;
   ctx->meta = meta;
   ctx->batch = batch;
   ctx->total_nodes = total;
@@ -795,10 +805,10 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   return CB_OK;
 }
 
-int cb_last_launch_info(cb_ctx* ctx, int32_t info[4]) {
+int cb_last_launch_info(cb_ctx* ctx, int32_t info[6]) {
   if (!ctx || !info) return set_err(ctx, CB_EINVAL, "null argument");
   if (!ctx->have_verify) return set_err(ctx, CB_ESTATE, "no verify call yet");
-  for (int i = 0; i < 4; i++) info[i] = ctx->launch_info[i];
+  for (int i = 0; i < 6; i++) info[i] = ctx->launch_info[i];
   return CB_OK;
 }
 

@@ -1164,7 +1164,7 @@ bool attn_mfma_can_fuse(const AttnParams& p, int max_nodes_in_call, int64_t logi
 }
 
 hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
-                            int total_nodes, const LogitsWork* logits_work) {
+                            int total_nodes, const LogitsWork* logits_work, int* merge_kind) {
   if (!attn_mfma_supports(p)) return hipErrorInvalidValue;
   const int g = p.Hq / p.Hkv;
   const int M = max_nodes_in_call * g;
@@ -1194,6 +1194,7 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
                   (int64_t)p.Hkv * tiles * p.batch <= kCoopTiles) ? 1 : 0;
   if (q.coop_merge) q.external_merge = 0;
   if (p.force_external_merge && p.nsplit > 1) { q.external_merge = 1; q.coop_merge = 0; }  // (option "external_merge": a test aid)
+  if (merge_kind) *merge_kind = p.nsplit <= 1 ? 0 : (q.coop_merge ? 1 : (q.external_merge ? 3 : 2));
   const bool ts = p.timeline != 0;  // (the timeline build of the same kernels: a measurement aid)
 #define CB_LAUNCH_ATTN(R, G, SEQ)                                                                           \
   do {                                                                                                      \

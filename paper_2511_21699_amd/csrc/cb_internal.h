@@ -203,7 +203,8 @@ size_t attn_mfma_partial_bytes(size_t max_total_nodes, int Hq, int Hkv, int max_
 bool attn_mfma_supports(const AttnParams& p);  // shape/geometry the MFMA kernel takes (bf16 is the caller's check)
 bool attn_mfma_can_fuse(const AttnParams& p, int max_nodes_in_call, int64_t logits_items, int logits_dtype);
 // with logits_work != nullptr (only if attn_mfma_can_fuse) the same launch also scans the logits and runs the acceptance
+// merge_kind (may be null): 0 one split, 1 cooperative merge, 2 merge by the last workgroup to arrive, 3 merge kernel
 hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& meta, int max_nodes_in_call,
-                            int total_nodes, const LogitsWork* logits_work);
+                            int total_nodes, const LogitsWork* logits_work, int* merge_kind);
 
 }  // namespace cb
