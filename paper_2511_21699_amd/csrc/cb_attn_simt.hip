@@ -54,7 +54,7 @@ __device__ __forceinline__ float dot_row(const float* __restrict__ sq, const T* 
 
 constexpr int kSimtTile = 1024;  // keys whose scores are held in LDS at a time
 
-// grid: x = split, y = node * Hq + head (node local to the sequence), z = sequence
+// grid: x = node * Hq + head (node local to the sequence), y = split, z = sequence
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_attn_simt(AttnParams p, SeqMeta meta) {
   __shared__ float sq[D];
