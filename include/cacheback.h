@@ -135,7 +135,13 @@ int cb_check_verify_args(const cb_config *cfg, int32_t batch, const cb_kv_layer 
  *                   at the root and at each accepted node in order (the last is the extra token a
  *                   pass always yields); the remaining entries are set to -1
  * Siblings may carry the same token; among accepted nodes of equal depth the lowest index wins.
- * Synchronises `hip_stream` (a hipStream_t, NULL = the null stream) before returning.
+ * Returns when accepted_len and accepted_tokens have arrived in host memory.  That can be before the
+ * launch on `hip_stream` (a hipStream_t, NULL = the null stream) has ended: the acceptance flags its
+ * results to the waiting host while the attention is still merging its splits.  attn_out is
+ * therefore complete in stream order, not on return: work enqueued on `hip_stream` afterwards sees
+ * it, a host read needs a synchronisation of the stream first.  A later call of this library on
+ * another stream waits for this one's launch by itself.  Option "full_sync" = 1 (cb_set_option)
+ * makes every call synchronise the stream before it returns.
  */
 int cb_verify_tree(cb_ctx *ctx, void *hip_stream, int32_t batch, const void *q,
                    const cb_kv_layer *kv, const int32_t *kv_len, const int32_t *node_offsets,
@@ -231,6 +237,8 @@ int cb_device_status(cb_ctx *ctx, int32_t *status);
  *   "merge_spin_limit"  how often a workgroup of a cooperative merge polls for the tile's other
  *                    splits before it leaves its slice to the workgroup that completes the tile
  *                    (default 256; 0 makes every workgroup but the completing one give up at once)
+ *   "full_sync"      1 = cb_verify_tree synchronises its stream before returning (default 0: it
+ *                    returns when the results have arrived, see there)
  *   "external_merge" 1 = always merge with the separate merge kernel
  *   "timeline"       1 = launch the timeline build of the MFMA kernels (see cb_debug_timestamps)
  *   "time_attention"  1 = record HIP events around the attention kernels (see cb_last_attention_ms) */

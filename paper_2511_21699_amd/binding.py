@@ -294,6 +294,14 @@ class Verifier:
                 self._raise(rc)
         return call
 
+    def bind_host_step(self, q, kv: CbKvLayer, logits, attn_out, batch: int = 1, layers: Sequence[CbKvLayer] = (),
+                       stream=None, parent=None, tokens=None) -> "HostStep":
+        """Pre-marshalled cb_verify_tree (+ cb_compact_kv): the caller fills the returned object's host arrays in
+        place and calls `verify()` / `compact()`, which only make the C calls (for decode loops, where per-call
+        marshalling would cost as much as the GPU work).  `parent` / `tokens`: int32 arrays to bind as the tree
+        (a TreeGrower's outputs, say) instead of arrays of the object's own."""
+        return HostStep(self, q, kv, logits, attn_out, batch, layers, stream, parent, tokens)
+
     def compact_kv(self, layers: Sequence[CbKvLayer], batch: int, want_len: bool = True, stream=None):
         arr = (CbKvLayer * len(layers))(*layers)
         new_len = np.zeros(batch, dtype=np.int32)
@@ -334,6 +342,45 @@ class Verifier:
         ms = C.c_float(0)
         self._raise(self.L.cb_last_attention_ms(self.ctx, C.byref(ms)))
         return ms.value
+
+
+class HostStep:
+    """One decode step through the host-array form, marshalled once.  Fill `kv_len`, `node_offsets`, `parent` and
+    `tokens` in place (int32, sized for the configuration's maxima), call `verify()`, read `accepted_len` and
+    `accepted_tokens`; `compact()` enqueues the compaction of the bound layers."""
+
+    def __init__(self, ver: "Verifier", q, kv, logits, attn_out, batch, layers, stream, parent=None, tokens=None):
+        cfg = ver.cfg
+        self._ver = ver
+        self.kv_len = np.zeros(batch, dtype=np.int32)
+        self.node_offsets = np.zeros(batch + 1, dtype=np.int32)
+        # (a drafter's own output arrays can be bound instead: then the tree needs no copy at all)
+        self.parent = np.zeros(cfg.max_batch * cfg.max_nodes, dtype=np.int32) if parent is None else parent
+        self.tokens = np.zeros(cfg.max_batch * cfg.max_nodes, dtype=np.int32) if tokens is None else tokens
+        for a in (self.parent, self.tokens):
+            if a.dtype != np.int32 or not a.flags.c_contiguous:
+                raise ValueError("parent and tokens must be contiguous int32 arrays")
+        self.accepted_len = np.zeros(batch, dtype=np.int32)
+        self.accepted_tokens = np.zeros((batch, ver.stride), dtype=np.int32)
+        st = ver._stream(stream)
+        self._kv = kv
+        self._layers = (CbKvLayer * len(layers))(*layers) if layers else None
+        self._keep = (q, logits, attn_out)
+        self._verify_args = (ver.ctx, st, batch, q.data_ptr(), C.byref(self._kv), _ip(self.kv_len), _ip(self.node_offsets),
+                             _ip(self.parent), _ip(self.tokens), logits.data_ptr(), attn_out.data_ptr(),
+                             _ip(self.accepted_len), _ip(self.accepted_tokens))
+        self._compact_args = (ver.ctx, st, len(layers), self._layers, None)
+        self._verify_fn, self._compact_fn = ver.L.cb_verify_tree, ver.L.cb_compact_kv
+
+    def verify(self):
+        rc = self._verify_fn(*self._verify_args)
+        if rc:
+            self._ver._raise(rc)
+
+    def compact(self):
+        rc = self._compact_fn(*self._compact_args)
+        if rc:
+            self._ver._raise(rc)
 
 
 # ----------------------------------------------------------------------------- host drafter (cacheback_drafter.h)

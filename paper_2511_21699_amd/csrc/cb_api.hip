@@ -122,6 +122,11 @@ struct cb_ctx {
   int32_t* h_path;
   int32_t* h_argmax;
   int32_t* h_misc;  // [0] status, [1..] new_len
+  int32_t* h_done;  // [max_batch] arrival flags of the host form's results (the call's sequence number)
+  int32_t call_seq = 0;        // sequence number of the last host-form call (never 0 once used)
+  int32_t* want_done = nullptr;  // set by cb_verify_tree for the launch it is about to make
+  hipStream_t unsynced = nullptr;  // stream that may still run the tail of a host-form call that has returned
+  bool have_unsynced = false;
   int32_t* d_hblock = nullptr;  // the pinned block's address on the device
   void* h_block;
   // state of the last verify
@@ -134,7 +139,7 @@ struct cb_ctx {
   int32_t last_len[CB_MAX_BATCH];
   hipStream_t last_stream;
   // options
-  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_timeline, opt_external, opt_fork, opt_fuse, opt_coop, opt_spin;
+  int64_t opt_splits, opt_impl, opt_time, opt_stages, opt_timeline, opt_external, opt_fork, opt_fuse, opt_coop, opt_spin, opt_full_sync;
   hipEvent_t ev0, ev1, ev_fork, ev_join;
   hipStream_t aux;  // second stream (default priority) for the logits scan beside the attention
   bool ev_valid;
@@ -292,6 +297,12 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   for (int b = 0; b < batch; b++) meta.kv_len[b] = kv_len[b];
   for (int b = 0; b <= batch; b++) meta.node_off[b] = node_offsets[b];
   const int total = node_offsets[batch];
+  if (ctx->have_unsynced && ctx->unsynced != st) {
+    // the last host-form call returned when its results arrived; what is left of its launch still uses
+    // the workspace, and only work on that same stream is ordered behind it
+    CB_HIP(ctx, hipStreamSynchronize(ctx->unsynced));
+    ctx->have_unsynced = false;
+  }
   if (ctx->counters_dirty) {  // (after a failed launch: the kernels rely on tickets that are zero between launches)
     const hipError_t e1 = launch_zero_words(st, ctx->dev<unsigned long long>(ctx->lay.tickets), ctx->lay.ticket_count / 2, 1, 1);
     const hipError_t e2 = launch_zero_words(st, ctx->dev<unsigned long long>(ctx->lay.coop_tickets), kCoopTiles, kCoopTicketStride / 8, 2);
@@ -349,6 +360,9 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   acc.len_ctx = ctx->dev<int32_t>(ctx->lay.len_ctx);
   acc.len_user = d_len;
   acc.tok_user = d_tok;
+  acc.done_flag = ctx->want_done;
+  acc.done_value = ctx->call_seq;
+  ctx->want_done = nullptr;
   // Small calls with the MFMA attention are one launch: the attention workgroups also scan the
   // logits and run the acceptance (option "fuse_logits", on by default; see attn_mfma_can_fuse).
   // Otherwise the scan, the attention and the acceptance are launches of their own.
@@ -540,7 +554,9 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   ctx->opt_coop = 1;
   ctx->opt_spin = 256;
   const size_t mt = lay.max_total_nodes, stride = (size_t)cfg->max_depth + 1;
-  const size_t ints = mt * 3 + cfg->max_batch * (1 + 2 * stride) + 1 + cfg->max_batch;
+  // (two tree areas: a host-form call may return while its kernels still run, and the next call
+  // must not overwrite the tree they read)
+  const size_t ints = mt * 5 + cfg->max_batch * (1 + 2 * stride) + 1 + 2 * (size_t)cfg->max_batch;
   hipError_t e = hipHostMalloc(&ctx->h_block, ints * 4, hipHostMallocDefault);
   if (e != hipSuccess) {
     delete ctx;
@@ -557,11 +573,14 @@ int cb_init(const cb_config* cfg, void* workspace, size_t workspace_bytes, cb_ct
   int32_t* h = static_cast<int32_t*>(ctx->h_block);
   ctx->h_parent = h; h += mt;
   ctx->h_tokens = h; h += mt;
+  h += 2 * mt;                       // (the second tree area, see cb_verify_tree)
   ctx->h_argmax = h; h += mt;
   ctx->h_len = h; h += cfg->max_batch;
   ctx->h_tok = h; h += cfg->max_batch * stride;
   ctx->h_path = h; h += cfg->max_batch * stride;
-  ctx->h_misc = h;
+  ctx->h_misc = h; h += 1 + cfg->max_batch;
+  ctx->h_done = h;
+  memset(ctx->h_done, 0, (size_t)cfg->max_batch * 4);
   e = hipEventCreate(&ctx->ev0);
   if (e == hipSuccess) e = hipEventCreate(&ctx->ev1);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
@@ -701,8 +720,12 @@ int cb_verify_tree(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, 
   // No copies: the kernels read the tree from, and write the results to, the context's pinned host
   // block through its device address (a few hundred bytes each way; two staged copies cost more
   // than the kernels' reads across the bus).  Parents and tokens back to back, lengths and tokens
-  // back to back.
-  int32_t* h_tree = ctx->h_parent;
+  // back to back.  Calls alternate between two tree areas: this call may return before its launch
+  // has ended (below), and the launch of the call before it has ended by the time this one's
+  // results arrive, because both run on one stream (run_pipeline synchronises when the stream changes).
+  const bool early = ctx->opt_full_sync == 0 && (ctx->opt_stages & 8) != 0;
+  ctx->call_seq = ctx->call_seq == INT32_MAX ? 1 : ctx->call_seq + 1;
+  int32_t* h_tree = ctx->h_parent + (size_t)(ctx->call_seq & 1) * 2 * ctx->lay.max_total_nodes;
   memcpy(h_tree, tree_parent, (size_t)total * 4);
   memcpy(h_tree + total, draft_tokens, (size_t)total * 4);
   int32_t* d_parent = ctx->d_hblock + (h_tree - static_cast<int32_t*>(ctx->h_block));
@@ -710,9 +733,41 @@ int cb_verify_tree(cb_ctx* ctx, void* hip_stream, int32_t batch, const void* q, 
   int32_t* h_res = ctx->h_len;
   int32_t* d_len = ctx->d_hblock + (h_res - static_cast<int32_t*>(ctx->h_block));
   int32_t* d_tok = d_len + batch;
+  if (early) ctx->want_done = ctx->d_hblock + (ctx->h_done - static_cast<int32_t*>(ctx->h_block));
   rc = run_pipeline(ctx, st, batch, q, kv, kv_len, node_offsets, d_parent, d_tokens, logits, attn_out, d_len, d_tok);
+  ctx->want_done = nullptr;
   if (rc) return rc;
-  CB_HIP(ctx, hipStreamSynchronize(st));
+  if (early) {
+    // The acceptance stores a sequence's results, makes them visible at system scope and then stores
+    // the call's number into the sequence's flag word; the host returns as soon as every flag shows
+    // it, without waiting for the rest of the launch (the attention's split merge) and for the
+    // stream's completion signal.  The stream's state is looked at now and then, so that a failed
+    // launch ends the wait.
+    const int32_t want = ctx->call_seq;
+    bool seen = false;
+    for (uint32_t polls = 1; !seen; polls++) {
+      seen = true;
+      for (int b = 0; b < batch; b++)
+        if (__atomic_load_n(ctx->h_done + b, __ATOMIC_ACQUIRE) != want) { seen = false; break; }
+      if (seen) break;
+      if ((polls & 2047) == 0) {
+        const hipError_t q_rc = hipStreamQuery(st);
+        if (q_rc == hipSuccess) {  // everything has run: the flags are there now or never
+          seen = true;
+          for (int b = 0; b < batch; b++)
+            if (__atomic_load_n(ctx->h_done + b, __ATOMIC_ACQUIRE) != want) seen = false;
+          if (!seen) return set_err(ctx, CB_EHIP, "the verification ran but its results did not arrive");
+        } else if (q_rc != hipErrorNotReady) {
+          return set_err(ctx, CB_EHIP, "%s: %s", "hipStreamQuery", hipGetErrorString(q_rc));
+        }
+      }
+      __builtin_ia32_pause();
+    }
+    ctx->unsynced = st;
+    ctx->have_unsynced = true;
+  } else {
+    CB_HIP(ctx, hipStreamSynchronize(st));
+  }
   memcpy(accepted_len, h_res, (size_t)batch * 4);
   memcpy(accepted_tokens, h_res + batch, (size_t)batch * stride * 4);
   memcpy(ctx->last_len, h_res, (size_t)batch * 4);
@@ -796,6 +851,7 @@ int cb_set_option(cb_ctx* ctx, const char* name, int64_t value) {
   else if (!strcmp(name, "time_attention")) ctx->opt_time = value;
   else if (!strcmp(name, "stages")) ctx->opt_stages = value & 15;
   else if (!strcmp(name, "timeline")) ctx->opt_timeline = value;
+  else if (!strcmp(name, "full_sync")) ctx->opt_full_sync = value;
   else if (!strcmp(name, "external_merge")) ctx->opt_external = value;
   else if (!strcmp(name, "parallel_scan")) ctx->opt_fork = value;
   else if (!strcmp(name, "fuse_logits")) ctx->opt_fuse = value;
@@ -832,6 +888,7 @@ const char* cb_last_error(const cb_ctx* ctx) { return ctx ? ctx->err : g_init_er
 
 void cb_destroy(cb_ctx* ctx) {
   if (!ctx) return;
+  if (ctx->have_unsynced) (void)hipStreamSynchronize(ctx->unsynced);  // its launch may still write the pinned block
   (void)hipEventDestroy(ctx->ev0);
   (void)hipEventDestroy(ctx->ev1);
   (void)hipEventDestroy(ctx->ev_fork);

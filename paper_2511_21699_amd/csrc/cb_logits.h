@@ -221,7 +221,18 @@ struct AcceptArgs {
   int32_t* len_ctx;        // [B] (kept for the compaction call)
   int32_t* len_user;       // [B]
   int32_t* tok_user;       // [B][max_depth + 1]
+  int32_t* done_flag;      // [B] or null: host-visible words that receive done_value once the sequence's
+  int32_t done_value;      // user results are visible to the host (the host form polls them)
 };
+
+// Tells a polling host that sequence b's results have arrived.  Called by every thread that wrote
+// results, after its stores: the system-scope release fence makes the wave's earlier stores visible
+// to the host before the flag store that follows can be.
+__device__ __forceinline__ void publish_done(const AcceptArgs& g, int b, bool writer) {
+  if (!g.done_flag) return;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
+  if (writer) __hip_atomic_store(as_global(g.done_flag) + b, g.done_value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
 template <bool COHERENT>
 __device__ __forceinline__ void accept_sequence(AcceptLds& sh, const AcceptArgs& g, int b, int off, int N) {
@@ -314,7 +325,9 @@ __device__ __forceinline__ void accept_sequence(AcceptLds& sh, const AcceptArgs&
     as_global(g.len_ctx)[b] = L;
     as_global(g.len_user)[b] = L;
   }
+  if (g.done_flag) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");  // every wave's result stores, before the barrier
   __syncthreads();
+  publish_done(g, b, t == 0);
 }
 
 // The same acceptance for a tree of at most 64 nodes by ONE wavefront (lane t owns node t; the
@@ -404,6 +417,7 @@ __device__ __forceinline__ void accept_wave(const AcceptArgs& g, int b, int off,
     as_global(g.len_ctx)[b] = L;
     as_global(g.len_user)[b] = L;
   }
+  publish_done(g, b, t == 0);
 }
 
 // The logits work of one verification call as a list of items (row, chunk), item = row * nchunks +
