@@ -73,7 +73,7 @@ def main():
     torch.cuda.set_device(0)
     if args.decode_loop:
         from paper_2511_21699_amd import decode_loop
-        print(json.dumps(decode_loop.run(steps=args.decode_loop, warmup=2000, **({"prompt_len": args.prefix} if args.prefix else {}))))
+        print(json.dumps(decode_loop.run(steps=args.decode_loop, warmup=400, **({"prompt_len": args.prefix} if args.prefix else {}))))
         return
     side = torch.cuda.Stream()          # a non-default stream: needed for graph capture, used for everything
 

@@ -81,14 +81,43 @@ def untracked_load_violations(asm: str) -> list:
     return bad
 
 
+def kernel_resources(asm: str) -> dict:
+    """{kernel symbol: (vgpr_count, vgpr_spill_count, private_segment_fixed_size)} from the listing's metadata."""
+    out, name, cur = {}, None, {}
+    for line in asm.split("\n"):
+        m = re.match(r"\s*(?:- )?\.(name|vgpr_count|vgpr_spill_count|private_segment_fixed_size):\s*(\S+)", line)
+        if not m:
+            continue
+        key, val = m.group(1), m.group(2)
+        if key == "name":
+            name = val
+        else:
+            cur[key] = int(val)
+        if name and len(cur) == 3:
+            out[name] = (cur["vgpr_count"], cur["vgpr_spill_count"], cur["private_segment_fixed_size"])
+            name, cur = None, {}
+    return out
+
+
+def scratch_violations(asm: str) -> list:
+    """Kernels of the listing that spill registers or use scratch memory.  In the attention kernel a spill
+    reload inside the K/V ring phase would be a compiler-generated load, and with it a wait for every load in
+    flight, in a loop whose waits are counted by hand."""
+    return [(k, v) for k, v in kernel_resources(asm).items() if v[1] != 0 or v[2] != 0]
+
+
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))
-    bad = untracked_load_violations(device_asm(os.path.join(CSRC, "cb_attn_mfma.hip")))
+    asm = device_asm(os.path.join(CSRC, "cb_attn_mfma.hip"))
+    bad = untracked_load_violations(asm)
     if bad:
         raise RuntimeError(f"cb_attn_mfma.hip: registers of untracked loads are touched before their wait: {bad[:4]}")
+    bad = scratch_violations(asm)
+    if bad:
+        raise RuntimeError(f"cb_attn_mfma.hip: kernels that spill or use scratch memory: {bad[:4]}")
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     if verbose:
         print(LIB)

@@ -42,3 +42,23 @@ def test_compiled_attention_kernel_passes():
     asm = build.device_asm(os.path.join(build.CSRC, "cb_attn_mfma.hip"))
     assert asm.count("global_load_lds_dwordx4") > 50          # the ring's requests are there, as inline assembly
     assert build.untracked_load_violations(asm) == []
+    res = build.kernel_resources(asm)
+    attn = {k: v for k, v in res.items() if "k_attn_mfma" in k or "k_verify_mfma" in k}
+    assert len(attn) == 8                                      # four variants, each with and without the timeline stamps
+    assert build.scratch_violations(asm) == []
+    assert all(v[0] <= 256 for v in attn.values())             # two waves per SIMD
+
+
+def test_scratch_checker_reports_spills():
+    meta = """
+  - .name:           k_good
+    .private_segment_fixed_size: 0
+    .vgpr_count:     200
+    .vgpr_spill_count: 0
+  - .name:           k_spills
+    .private_segment_fixed_size: 864
+    .vgpr_count:     256
+    .vgpr_spill_count: 216
+"""
+    assert build.kernel_resources(meta) == {"k_good": (200, 0, 0), "k_spills": (256, 216, 864)}
+    assert [k for k, _ in build.scratch_violations(meta)] == ["k_spills"]
