@@ -252,6 +252,40 @@ Plan plan_attention(const cb_config& c, int max_splits, int scalar_splits, int o
       return (double)keys / ((double)rounds * 256.0 * chunk);
     };
     const int cap = (int)std::max<int64_t>(1, std::min<int64_t>(max_splits, (p.max_len + 127) / 128));
+    const int tiles_max = (mrows + rows_per_wg - 1) / rows_per_wg;
+    if (batch > 1 && (c.num_kv_heads * tiles_max) % 8 == 0) {
+      // Several sequences, launched longest first within every XCD (see the kernel's workgroup
+      // numbering).  Such a list schedule ends no later than max(longest job, work / units + a job
+      // of the shortest sequence), so: estimate that for every split count, in units of one 64-key
+      // stage, with what a workgroup costs beside its stages (start-up and tail: about six stages;
+      // a workgroup of the grid that finds no keys: one), and what a tile's merge costs its last
+      // workgroup, and take the cheapest count -- the fewest splits that still spread the longest
+      // sequence wide enough.
+      double best_cost = 0.0;
+      nsplit = 1;
+      for (int ns = 1; ns <= cap; ns++) {
+        const int chunk = ((p.max_len + ns - 1) / ns + 31) / 32 * 32;
+        const int grid_x = (p.max_len + chunk - 1) / chunk;
+        const double merge = grid_x > 1 ? 0.7 * grid_x * (rows_per_wg / 128.0) : 0.0;
+        double work = 0.0, longest = 0.0, shortest = 1e30;
+        int64_t jobs = 0;
+        for (int b = 0; b < batch; b++) {
+          const int n = node_offsets[b + 1] - node_offsets[b];
+          const int len = kv_len[b] + n;
+          const int64_t tl = (int64_t)((n * g + rows_per_wg - 1) / rows_per_wg) * c.num_kv_heads;
+          const int full = len / chunk, rest = len - full * chunk;
+          const double job_full = 6.0 + (chunk + 63) / 64, job_rest = rest > 0 ? 6.0 + (rest + 63) / 64 : 0.0;
+          const int real = full + (rest > 0 ? 1 : 0);
+          work += tl * (full * job_full + job_rest + (real > 1 ? merge : 0.0)) +
+                  ((int64_t)c.num_kv_heads * tiles_max * grid_x - tl * real) * 1.0;
+          jobs += tl * real;
+          longest = std::max(longest, (full > 0 ? job_full : job_rest) + (real > 1 ? merge : 0.0));
+          shortest = std::min(shortest, full > 0 ? job_full : job_rest);
+        }
+        const double cost = jobs <= 256 ? longest : std::max(longest, work / 256.0 + shortest);
+        if (ns == 1 || cost < best_cost - 1e-9) { best_cost = cost; nsplit = ns; }
+      }
+    } else {
     nsplit = cap;
     double best = -1.0;
     for (int ns = 1; ns <= cap; ns++) {
@@ -266,6 +300,7 @@ Plan plan_attention(const cb_config& c, int max_splits, int scalar_splits, int o
         const double eff = efficiency(ns);
         if (eff > best + 1e-9) { best = eff; nsplit = ns; }
       }
+    }
     }
   }
   nsplit = std::max(1, std::min(nsplit, max_splits));
@@ -296,6 +331,10 @@ int run_pipeline(cb_ctx* ctx, hipStream_t st, int batch, const void* q, const cb
   SeqMeta meta{};
   for (int b = 0; b < batch; b++) meta.kv_len[b] = kv_len[b];
   for (int b = 0; b <= batch; b++) meta.node_off[b] = node_offsets[b];
+  for (int b = 0; b < batch; b++) meta.by_length[b] = b;
+  std::stable_sort(meta.by_length, meta.by_length + batch, [&](int32_t x, int32_t y) {
+    return (int64_t)kv_len[x] + node_offsets[x + 1] - node_offsets[x] > (int64_t)kv_len[y] + node_offsets[y + 1] - node_offsets[y];
+  });
   const int total = node_offsets[batch];
   if (ctx->have_unsynced && ctx->unsynced != st) {
     // the last host-form call returned when its results arrived; what is left of its launch still uses

@@ -535,11 +535,24 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p_arg, const SeqMeta
   {
     const int T = p.grid_x * p.grid_y * p.grid_z;
     const int d = blockIdx.x + p.grid_x * (blockIdx.y + p.grid_y * blockIdx.z);
-    const int j = p.xcd_remap ? (d & 7) * (T >> 3) + (d >> 3) : d;
-    split = j % p.grid_x;
-    const int rest = j / p.grid_x;
-    b = rest % p.grid_z;
-    by = rest / p.grid_z;
+    if (p.xcd_remap == 2) {
+      // XCD x = d % 8 works through position r = d / 8 of its own list: all splits of a tile together,
+      // the tiles of one sequence together, the sequences from the longest to the shortest -- so the
+      // workgroups that are dispatched last, and decide when the launch ends, are the short ones.  The
+      // XCD's tiles are the same grid_y / 8 (kv head, row tile) pairs of every sequence.
+      const int x = d & 7, r = d >> 3;
+      split = r % p.grid_x;
+      const int tile = r / p.grid_x;
+      const int ypx = p.grid_y >> 3;
+      by = x * ypx + tile % ypx;
+      b = __builtin_amdgcn_readlane(ml.ord, tile / ypx);
+    } else {
+      const int j = p.xcd_remap ? (d & 7) * (T >> 3) + (d >> 3) : d;
+      split = j % p.grid_x;
+      const int rest = j / p.grid_x;
+      b = rest % p.grid_z;
+      by = rest / p.grid_z;
+    }
   }
   // (row tiles of one kv head are neighbours in j: they sweep the same K/V and then share an XCD's L2)
   const int tiles = p.grid_y / p.Hkv;
@@ -1175,6 +1188,7 @@ hipError_t launch_attn_mfma(hipStream_t st, const AttnParams& p, const SeqMeta& 
   const int64_t T = (int64_t)p.nsplit * p.Hkv * tiles * p.batch;
   // renumbering needs whole groups of splits inside each XCD's share of the grid
   q.xcd_remap = (T % 8 == 0 && (T / 8) % p.nsplit == 0) ? 1 : 0;
+  if (grid.y % 8 == 0 && p.batch > 1) q.xcd_remap = 2;  // (several sequences: longest first within every XCD)
   q.grid_x = grid.x;
   q.grid_y = grid.y;
   q.grid_z = grid.z;

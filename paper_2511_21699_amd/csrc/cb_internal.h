@@ -19,6 +19,7 @@ constexpr int partial_stride(int D) { return D + 4; }
 struct SeqMeta {
   int32_t kv_len[CB_MAX_BATCH];
   int32_t node_off[CB_MAX_BATCH + 1];
+  int32_t by_length[CB_MAX_BATCH];  // the sequences ordered by kv_len + nodes, longest first (filled by the host)
 };
 
 // Shapes of sequence `b` (uniform in the wave) without a dependent scalar load: every lane fetches
@@ -29,7 +30,7 @@ struct SeqShape {
   int S, off, N;
 };
 struct SeqMetaLanes {
-  int kv, o0, o1;
+  int kv, o0, o1, ord;
 };
 __device__ __forceinline__ SeqMetaLanes seq_meta_prefetch(const SeqMeta& meta) {
   const int lane = threadIdx.x & 63;
@@ -37,6 +38,7 @@ __device__ __forceinline__ SeqMetaLanes seq_meta_prefetch(const SeqMeta& meta) {
   r.kv = meta.kv_len[lane];
   r.o0 = meta.node_off[lane];
   r.o1 = meta.node_off[lane + 1];
+  r.ord = meta.by_length[lane];
   return r;
 }
 __device__ __forceinline__ SeqShape seq_shape(const SeqMetaLanes& m, int b) {
@@ -161,7 +163,8 @@ struct AttnParams {
   int32_t nsplit;       // partial slots per row (>= splits any sequence uses)
   int32_t batch;
   float scale;
-  int32_t xcd_remap;    // 1: renumber workgroups so that all splits of a tile run on one XCD
+  int32_t xcd_remap;    // 1: renumber workgroups so that all splits of a tile run on one XCD; 2: and every XCD takes
+                        // its share -- a fixed set of (kv head, row tile) pairs of all sequences -- longest sequence first
   int32_t grid_x, grid_y, grid_z;  // launch grid, repeated here so the kernel reads one argument block
   int32_t external_merge;  // 1: the kernel only writes partials; launch_attn_mfma runs a merge kernel afterwards
   int32_t coop_merge;      // 1: every workgroup of a tile merges a slice of it after a bounded wait for the others

@@ -109,6 +109,16 @@ def test_split_counts_agree_with_the_oracle(splits, merge):
              expect_status=32 if (merge == "gave_up" and splits > 1) else 0)
 
 
+@pytest.mark.parametrize("splits", [2, 3, 7])
+def test_ragged_batch_with_forced_splits(splits):
+    # several sequences of unequal length are launched longest first within every XCD, and by default
+    # with as few splits as spread the longest one (often a single one): here the splits, and with
+    # them the tiles' merges and the workgroups that find no keys, are forced
+    case = W.make_config(4, B=6, S=(200, 3000), V=2048)
+    run_case(case, options={"splits": splits}, what=f"ragged batch, {splits} splits")
+    run_case(case, options={"splits": splits, "fuse_logits": 0, "coop_merge": 0}, what=f"ragged batch, {splits} splits, separate launches")
+
+
 @pytest.mark.parametrize("opts", [{}, {"coop_merge": 0}, {"fuse_logits": 0}, {"fuse_logits": 0, "coop_merge": 0}])
 def test_merge_across_xcds(opts):
     """15 workgroups (3 kv heads x 5 splits) cannot be renumbered into whole tiles per XCD, so the splits of a
